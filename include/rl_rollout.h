@@ -1,0 +1,163 @@
+/*
+ * rl_rollout.h - C boundary of the batched multi-turn rollout engine (one GPU).
+ *
+ * The engine runs the GPU part of the "Generate - Parse - Invoke - Update" loop of the
+ * paper's Section 2.3.2: Generate = rl_decode_step repeated, Update = rl_append_observation,
+ * termination of a trajectory (Section 2.2, last paragraph; Section 2.3.2 Parse step: no tool
+ * call found) = rl_release.  A trajectory is the interleaving of model-generated chunks X and
+ * observation chunks O of Section 2.2; the engine keeps, per trajectory, the tokens, the
+ * observation mask (1 = appended from outside, 0 = sampled by the policy; observation tokens
+ * do not take part in the loss, Section 2.2 / "Loss Mask" in Section 2.3.2) and the log-prob
+ * of every sampled token.
+ *
+ * General rules
+ *  - All pointers in the signatures are HOST pointers; the library owns every device buffer.
+ *  - The caller owns every buffer it passes in or receives results in.
+ *  - Every function returns 0 (RL_OK) or a negative rl_status; a failing call changes no
+ *    trajectory or allocator state (pages are reserved for the whole call before any write).
+ *    rl_last_error() gives a thread-local message for the last failure.
+ *  - Calls are synchronous: results are in the output buffers when the call returns.
+ *  - One caller thread per rl_model; different models are independent.
+ *  - Trajectory ids are arbitrary non-negative int32 chosen by the caller.
+ */
+#ifndef RL_ROLLOUT_H
+#define RL_ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rl_model rl_model;
+
+typedef enum {
+  RL_OK = 0,
+  RL_E_ARG = -1,          /* null pointer, negative count / id / temperature, bad config */
+  RL_E_BAD_TRAJ = -2,     /* unknown trajectory id */
+  RL_E_DUP_ID = -3,       /* the same id twice in one call, or a fork destination that exists */
+  RL_E_BAD_TOKEN = -4,    /* token id outside [0, vocab) */
+  RL_E_NOPAGES = -5,      /* KV page pool exhausted */
+  RL_E_CTX_OVERFLOW = -6, /* a trajectory would exceed max_context */
+  RL_E_EMPTY = -7,        /* decode on a trajectory without any token */
+  RL_E_HIP = -8,          /* a HIP runtime call failed */
+  RL_E_TOO_MANY = -9      /* more live trajectories than max_trajectories */
+} rl_status;
+
+/* Decoder shape, as stored in the weight blob's header. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab;
+  float rms_eps, rope_theta;
+  int32_t qk_norm;        /* 1: per-head RMSNorm on q and k before RoPE */
+  int32_t tie_embeddings; /* 1: lm-head shares the embedding matrix */
+  int32_t weight_dtype;   /* 0: fp32 weights, fp32 arithmetic and cache; 1: bf16 weights,
+                             bf16 activations / cache, fp32 accumulation and residual */
+} rl_model_config;
+
+typedef struct {
+  int32_t page_tokens;      /* tokens per KV page; must be 16 */
+  int32_t max_context;      /* longest trajectory, in tokens */
+  int32_t max_trajectories; /* live trajectories at any time */
+  int64_t kv_pool_pages;    /* pages in the pool (each holds page_tokens tokens of every layer) */
+  int32_t max_batch_rows;   /* rows processed per internal pass of an append (0: default 8192) */
+  int32_t flags;            /* RL_FLAG_* */
+} rl_runtime_config;
+
+#define RL_FLAG_GENERIC_KERNELS 1 /* bf16 models: use the shape-generic kernels even where the
+                                     MFMA kernels apply (testing) */
+
+/*
+ * Load a model: parse the blob (64-byte header: "RLW1", u32 version 1, the rl_model_config
+ * fields in declaration order, zero padding; then tensors back to back, row-major [out, in]:
+ * embed[V,H]; per layer g_in[H] W_q W_k W_v g_q[d] g_k[d] W_o g_post[H] W_gate W_up W_down;
+ * g_final[H]; lm_head[V,H] unless tied), copy and repack the weights into device memory,
+ * build the RoPE table and allocate the KV page pool.  `weights` may be freed on return.
+ * Errors: RL_E_ARG (bad header / size / config), RL_E_HIP (allocation).
+ */
+int rl_model_load(const rl_runtime_config* rt, const void* weights, size_t nbytes,
+                  rl_model** out);
+void rl_model_free(rl_model* m);
+int rl_model_get_config(const rl_model* m, rl_model_config* out);
+const char* rl_last_error(void);
+
+/*
+ * Update step (Section 2.3.2): append lens[i] tokens (observation tokens, or the prompt) to
+ * trajectory traj_ids[i]; `tokens` is the concatenation in call order.  Unknown ids are
+ * created.  Every appended token gets mask 1 and no log-prob.  The tokens' keys / values are
+ * computed by chunked prefill into the paged cache.  Pages are taken lowest-free-index first,
+ * trajectories in call order.  lens[i] = 0 is allowed.
+ * Errors: ARG, DUP_ID, BAD_TOKEN, CTX_OVERFLOW, TOO_MANY, NOPAGES, HIP.
+ */
+int rl_append_observation(rl_model* m, const int32_t* traj_ids, int32_t n,
+                          const int32_t* tokens, const int32_t* lens);
+
+/*
+ * Generate step (Section 2.3.2; a_t ~ pi_theta(. | s_t), Section 2.2): one new token for each
+ * listed trajectory.  The token is drawn from softmax(logits / temperature) by integer
+ * inverse CDF at the 32-bit uniform rl_uniform_u32(rng_seed, traj_id, index of the new token);
+ * temperature 0 selects the arg-max (lowest index on ties).  token_ids_out[i] and
+ * logprobs_out[i] (log-prob under the temperature-scaled distribution; temperature 0 reports
+ * it at temperature 1) are in call order.  The token is appended with mask 0.
+ * Errors: ARG, BAD_TRAJ, DUP_ID, EMPTY, CTX_OVERFLOW, NOPAGES, HIP.
+ */
+int rl_decode_step(rl_model* m, const int32_t* active_traj_ids, int32_t n, float temperature,
+                   uint64_t rng_seed, int32_t* token_ids_out, float* logprobs_out);
+
+/* Trajectory ended: give its pages back (shared pages when their last holder lets go). */
+int rl_release(rl_model* m, const int32_t* traj_ids, int32_t n);
+
+/* ---- auxiliaries --------------------------------------------------------------------- */
+
+/*
+ * Group sampling (Section 2.3, the GRPO example: several trajectories continue one prompt):
+ * create dst_ids[0..n) as copies of trajectory `src`.  Pages lying entirely before src's last
+ * token are shared by reference count; the remaining page is copied into a fresh page per
+ * destination.  Errors: ARG, BAD_TRAJ, DUP_ID, TOO_MANY, NOPAGES, HIP.
+ */
+int rl_fork(rl_model* m, int32_t src, const int32_t* dst_ids, int32_t n);
+
+int rl_traj_info(rl_model* m, int32_t traj_id, int32_t* n_tokens, int32_t* n_pages);
+/* Any output may be NULL; non-NULL ones must hold n_tokens (pages: n_pages) entries.
+ * logprobs[t] is 0 where obs_mask[t] = 1. */
+int rl_traj_read(rl_model* m, int32_t traj_id, int32_t* tokens, uint8_t* obs_mask,
+                 float* logprobs, int32_t* pages);
+int64_t rl_free_pages(const rl_model* m);
+
+/*
+ * Teacher-forced full-trajectory pass (the log-prob recomputation that consumes the loss
+ * mask): for each listed trajectory with n tokens writes n floats, out[t] = log softmax(
+ * z_{t-1} / temperature)[x_t] where x_t was sampled (mask 0), 0 where it was appended (mask 1)
+ * and at t = 0; trajectories are concatenated in call order.  Temperature 0 means 1.
+ */
+int rl_recompute_logprobs(rl_model* m, const int32_t* traj_ids, int32_t n, float temperature,
+                          float* out);
+
+/* Parity aids.  rl_debug_logits: next-token logits [vocab] of one trajectory, no state change.
+ * rl_decode_step_forced: a decode step that appends forced_token_ids[i] instead of sampling and
+ * returns its log-prob. */
+int rl_debug_logits(rl_model* m, int32_t traj_id, float* logits_out);
+int rl_decode_step_forced(rl_model* m, const int32_t* traj_ids, int32_t n, float temperature,
+                          const int32_t* forced_token_ids, float* logprobs_out);
+
+/* The sampler in isolation, on the GPU: `rows` rows of `vocab` float32 logits (host), one
+ * uniform per row.  Same arithmetic as inside rl_decode_step. */
+int rl_sample_from_logits(const float* logits, int32_t rows, int32_t vocab, float temperature,
+                          const uint32_t* u32, int32_t* ids_out, float* logprobs_out);
+/* SplitMix64 output number ((traj_id << 32) | position) + 1 from state `seed`, top 32 bits. */
+uint32_t rl_uniform_u32(uint64_t seed, int32_t traj_id, int32_t position);
+
+/*
+ * Kernel timing for benchmarks: when enabled, every `every`-th decode step brackets its
+ * decode-attention launches with HIP events on the engine's stream.  rl_timing_read returns
+ * the accumulated duration, the number of timed launches and the bytes of keys / values
+ * those launches had to read (sum over rows of context length x bytes per token per layer).
+ */
+int rl_timing_enable(rl_model* m, int32_t every);
+int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches, double* attn_kv_bytes,
+                   int reset);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RL_ROLLOUT_H */

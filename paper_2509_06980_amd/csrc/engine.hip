@@ -1,0 +1,926 @@
+// Runtime behind the C boundary: weight store, paged KV pool, trajectory records, and the
+// sequencing of kernels for the Generate (decode) and Update (append) steps of the paper's
+// rollout loop (Section 2.3.2).  Host code only; kernels live in kernels_*.hip.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <functional>
+#include <queue>
+#include <string>
+#include <unordered_map>
+#include <unordered_set>
+#include <vector>
+
+#include "../../include/rl_rollout.h"
+#include "kernels.h"
+
+static thread_local std::string g_err;
+static int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+extern "C" const char* rl_last_error(void) { return g_err.c_str(); }
+
+#define HIPCHECK(expr)                                                                      \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail(RL_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));             \
+  } while (0)
+
+namespace {
+
+struct Traj {
+  int slot = -1;
+  int n_cached = 0;  // keys / values of tokens[0 .. n_cached) are in the cache
+  std::vector<int32_t> tokens;
+  std::vector<uint8_t> mask;
+  std::vector<float> logp;
+  std::vector<int32_t> pages;
+};
+
+struct LayerW {
+  void *g_in, *wqkv, *gq, *gk, *wo, *g_post, *wgu, *wdown;
+};
+
+template <typename T>
+static inline T* dptr(void* p) { return (T*)p; }
+
+}  // namespace
+
+struct rl_model {
+  rl_model_config cfg{};
+  rl_runtime_config rt{};
+  ModelDims md{};
+  bool bf16 = false, mfma = false;
+  size_t el = 4;
+  hipStream_t stream = nullptr;
+  std::vector<void*> allocs;  // everything to hipFree
+  // weights
+  void *embed = nullptr, *lm_head = nullptr, *g_final = nullptr;
+  std::vector<LayerW> layers;
+  float* rope_cs = nullptr;
+  // cache
+  std::vector<KvPool> pools;
+  size_t page_bytes = 0;  // one page of one layer, K (or V) only
+  int32_t* page_table = nullptr;
+  // work buffers
+  int Mcap = 0, Rl = 0, rows_per_item = 1;
+  float *h = nullptr, *qkv = nullptr, *gu = nullptr, *logits = nullptr, *attn_scratch = nullptr;
+  void *xa = nullptr, *xo = nullptr, *xm = nullptr, *qb = nullptr;
+  int32_t *d_meta = nullptr, *h_meta = nullptr;  // device / pinned staging for per-call integers
+  size_t meta_ints = 0;
+  SamplerScratch ss{};
+  int32_t *d_ids = nullptr, *h_ids = nullptr;
+  float *d_lp = nullptr, *h_lp = nullptr;
+  uint8_t* d_mask = nullptr;
+  int max_attn_splits = 16;
+  // host state
+  std::unordered_map<int32_t, Traj> traj;
+  std::vector<int> free_slots;
+  std::priority_queue<int, std::vector<int>, std::greater<int>> free_pages;
+  std::vector<int32_t> refcount;
+  int64_t n_free = 0;
+  // timing
+  int timing_every = 0;
+  int64_t decode_steps = 0, attn_launches = 0;
+  double attn_ms = 0.0, attn_bytes = 0.0;
+  std::vector<hipEvent_t> ev;
+
+  int dalloc(void** p, size_t bytes, bool zero = false) {
+    if (bytes == 0) bytes = 16;
+    HIPCHECK(hipMalloc(p, bytes));
+    allocs.push_back(*p);
+    if (zero) HIPCHECK(hipMemset(*p, 0, bytes));
+    return RL_OK;
+  }
+};
+
+namespace {
+
+int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+// Offsets (in elements) of the blob's tensors.
+struct BlobMap {
+  size_t embed, g_final, lm_head;
+  struct L { size_t g_in, w_q, w_k, w_v, g_q, g_k, w_o, g_post, w_gate, w_up, w_down; };
+  std::vector<L> layers;
+  size_t total;
+};
+
+BlobMap map_blob(const rl_model_config& c) {
+  BlobMap m;
+  size_t off = 0;
+  size_t H = c.hidden, d = c.head_dim, I = c.intermediate, V = c.vocab;
+  size_t qw = (size_t)c.n_q_heads * d, kw = (size_t)c.n_kv_heads * d;
+  auto take = [&](size_t n) { size_t o = off; off += n; return o; };
+  m.embed = take(V * H);
+  for (int l = 0; l < c.n_layers; l++) {
+    BlobMap::L x;
+    x.g_in = take(H); x.w_q = take(qw * H); x.w_k = take(kw * H); x.w_v = take(kw * H);
+    x.g_q = take(d); x.g_k = take(d); x.w_o = take(H * qw); x.g_post = take(H);
+    x.w_gate = take(I * H); x.w_up = take(I * H); x.w_down = take(H * I);
+    m.layers.push_back(x);
+  }
+  m.g_final = take(H);
+  m.lm_head = c.tie_embeddings ? m.embed : take(V * H);
+  m.total = off;
+  return m;
+}
+
+bool mfma_shape_ok(const rl_model_config& c) {
+  int g = c.n_q_heads / c.n_kv_heads;
+  bool pow2 = g >= 1 && g <= 16 && (g & (g - 1)) == 0;
+  int qw = c.n_q_heads * c.head_dim, kvw = c.n_kv_heads * c.head_dim;
+  return c.weight_dtype == 1 && c.head_dim == 128 && pow2 && c.hidden % 64 == 0 &&
+         c.intermediate % 64 == 0 && qw % 64 == 0 && (qw + 2 * kvw) % 32 == 0 &&
+         c.hidden % 32 == 0 && c.vocab % 32 == 0;
+}
+
+// ---- one pass of the decoder over M batch rows ----------------------------------------------
+// Row metadata (device): tok, pos, slot.  Leaves the residual stream in m->h.
+struct RowMeta {
+  const int32_t *tok, *pos, *slot;
+  const AttnItem* items;
+  int n_items;
+  int attn_splits;
+  double kv_bytes;   // keys + values the attention of one layer has to read
+  bool time_attn;
+};
+
+template <typename TW, typename TA>
+void forward_generic(rl_model* m, int M, const RowMeta& r) {
+  hipStream_t s = m->stream;
+  const ModelDims& md = m->md;
+  int H = md.H, qw = md.nq * md.d, kvw = md.nkv * md.d, I = md.I;
+  launch_embed<TW>(s, (const TW*)m->embed, r.tok, m->h, M, H);
+  for (int l = 0; l < md.L; l++) {
+    const LayerW& w = m->layers[l];
+    launch_rmsnorm<TW, TA>(s, m->h, (const TW*)w.g_in, (TA*)m->xa, M, H, md.eps, false);
+    launch_gemm_generic<TA, TW>(s, (const TA*)m->xa, (const TW*)w.wqkv, m->qkv, M, qw + 2 * kvw, H, false);
+    launch_qkrope<TW, TA, TA, false>(s, m->qkv, (const TW*)w.gq, (const TW*)w.gk, m->rope_cs, r.pos,
+                                     r.slot, m->page_table, (TA*)m->qb, m->pools[l], md, M, false);
+    if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
+    launch_attention_generic<TA, TA, false>(s, (const TA*)m->qb, m->pools[l], r.pos, r.slot,
+                                            m->page_table, (TA*)m->xo, md, M, false);
+    if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
+    launch_gemm_generic<TA, TW>(s, (const TA*)m->xo, (const TW*)w.wo, m->h, M, H, qw, true);
+    launch_rmsnorm<TW, TA>(s, m->h, (const TW*)w.g_post, (TA*)m->xa, M, H, md.eps, false);
+    launch_gemm_generic<TA, TW>(s, (const TA*)m->xa, (const TW*)w.wgu, m->gu, M, 2 * I, H, false);
+    launch_swiglu<TA>(s, m->gu, (TA*)m->xm, M, I, false);
+    launch_gemm_generic<TA, TW>(s, (const TA*)m->xm, (const TW*)w.wdown, m->h, M, H, I, true);
+  }
+}
+
+int gemm_splits(int M, int N, int K) {
+  int tiles = ((N + 127) / 128) * ((M + 127) / 128);
+  int want = (512 + tiles - 1) / tiles;
+  int max_s = std::max(1, K / 128);          // at least two 64-k chunks per split
+  return std::max(1, std::min(want, max_s));
+}
+
+void forward_mfma(rl_model* m, int M, const RowMeta& r) {
+  hipStream_t s = m->stream;
+  const ModelDims& md = m->md;
+  int H = md.H, qw = md.nq * md.d, kvw = md.nkv * md.d, I = md.I;
+  launch_embed<bf16_t>(s, (const bf16_t*)m->embed, r.tok, m->h, M, H);
+  for (int l = 0; l < md.L; l++) {
+    const LayerW& w = m->layers[l];
+    launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)w.g_in, (bf16_t*)m->xa, M, H, md.eps, true);
+    int sq = gemm_splits(M, qw + 2 * kvw, H);
+    launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wqkv, m->qkv, M, qw + 2 * kvw, H,
+                     sq > 1 ? EPI_ATOMIC_ADD : EPI_STORE, sq);
+    launch_qkrope<bf16_t, bf16_t, bf16_t, true>(s, m->qkv, (const bf16_t*)w.gq, (const bf16_t*)w.gk,
+                                                m->rope_cs, r.pos, r.slot, m->page_table,
+                                                (bf16_t*)m->qb, m->pools[l], md, M, true);
+    if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
+    launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, m->page_table,
+                          (bf16_t*)m->xo, m->attn_scratch, md, r.attn_splits);
+    if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
+    launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->h, M, H, qw, EPI_ATOMIC_ADD,
+                     gemm_splits(M, H, qw));
+    launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)w.g_post, (bf16_t*)m->xa, M, H, md.eps, true);
+    launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wgu, m->xm, M, 2 * I, H, EPI_SWIGLU, 1);
+    launch_gemm_mfma(s, (const bf16_t*)m->xm, (const bf16_t*)w.wdown, m->h, M, H, I, EPI_ATOMIC_ADD,
+                     gemm_splits(M, H, I));
+  }
+}
+
+void forward_rows(rl_model* m, int M, const RowMeta& r) {
+  if (m->mfma) forward_mfma(m, M, r);
+  else if (m->bf16) forward_generic<bf16_t, bf16_t>(m, M, r);
+  else forward_generic<float, float>(m, M, r);
+}
+
+// final norm + lm-head for rows [r0, r0 + R) of m->h -> m->logits[0 .. R)
+void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done) {
+  hipStream_t s = m->stream;
+  const ModelDims& md = m->md;
+  if (m->mfma) {
+    if (!norm_done)
+      launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, M, md.H, md.eps, true);
+    // r0 is a multiple of 128: skip whole A tiles
+    launch_gemm_mfma(s, (const bf16_t*)m->xa + (size_t)r0 * md.H, (const bf16_t*)m->lm_head, m->logits,
+                     R, md.V, md.H, EPI_STORE, 1);
+  } else if (m->bf16) {
+    if (!norm_done)
+      launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, M, md.H, md.eps, false);
+    launch_gemm_generic<bf16_t, bf16_t>(s, (const bf16_t*)m->xa + (size_t)r0 * md.H,
+                                        (const bf16_t*)m->lm_head, m->logits, R, md.V, md.H, false);
+  } else {
+    if (!norm_done)
+      launch_rmsnorm<float, float>(s, m->h, (const float*)m->g_final, (float*)m->xa, M, md.H, md.eps, false);
+    launch_gemm_generic<float, float>(s, (const float*)m->xa + (size_t)r0 * md.H,
+                                      (const float*)m->lm_head, m->logits, R, md.V, md.H, false);
+  }
+}
+
+// ---- per-call metadata staging ----------------------------------------------------------------
+// Layout of the integer staging buffer for a pass over M rows:
+//   [0,M) tok  [M,2M) pos  [2M,3M) slot  [3M,4M) traj id  [4M,5M) index of the new token
+//   [5M,6M) forced / target ids  [6M, 6M + 4 * n_items) attention items
+struct Staging {
+  std::vector<int32_t> tok, pos, slot, traj, newpos, forced;
+  std::vector<AttnItem> items;
+  std::vector<uint8_t> mask;
+  void clear() { tok.clear(); pos.clear(); slot.clear(); traj.clear(); newpos.clear(); forced.clear(); items.clear(); mask.clear(); }
+};
+
+struct DevMeta {
+  int32_t *tok, *pos, *slot, *traj, *newpos, *forced;
+  AttnItem* items;
+};
+
+int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
+  size_t M = st.tok.size();
+  size_t need = 6 * M + 4 * st.items.size();
+  if (need > m->meta_ints) return fail(RL_E_ARG, "internal: metadata staging too small");
+  int32_t* h = m->h_meta;
+  auto put = [&](const std::vector<int32_t>& v, size_t at) {
+    if (!v.empty()) memcpy(h + at, v.data(), v.size() * 4);
+  };
+  put(st.tok, 0); put(st.pos, M); put(st.slot, 2 * M); put(st.traj, 3 * M); put(st.newpos, 4 * M);
+  put(st.forced, 5 * M);
+  if (!st.items.empty()) memcpy(h + 6 * M, st.items.data(), st.items.size() * sizeof(AttnItem));
+  HIPCHECK(hipMemcpyAsync(m->d_meta, h, need * 4, hipMemcpyHostToDevice, m->stream));
+  dm->tok = m->d_meta; dm->pos = m->d_meta + M; dm->slot = m->d_meta + 2 * M;
+  dm->traj = m->d_meta + 3 * M; dm->newpos = m->d_meta + 4 * M; dm->forced = m->d_meta + 5 * M;
+  dm->items = (AttnItem*)(m->d_meta + 6 * M);
+  if (!st.mask.empty())
+    HIPCHECK(hipMemcpyAsync(m->d_mask, st.mask.data(), st.mask.size(), hipMemcpyHostToDevice, m->stream));
+  return RL_OK;
+}
+
+// page-table updates (slot, index, page) -> device, in batches through the staging buffer
+int push_page_updates(rl_model* m, const std::vector<int32_t>& upd) {
+  size_t n = upd.size() / 3, done = 0;
+  size_t cap = m->meta_ints / 3;
+  while (done < n) {
+    size_t k = std::min(cap, n - done);
+    memcpy(m->h_meta, upd.data() + 3 * done, k * 12);
+    HIPCHECK(hipMemcpyAsync(m->d_meta, m->h_meta, k * 12, hipMemcpyHostToDevice, m->stream));
+    launch_page_table_update(m->stream, m->page_table, m->d_meta, (int)k, m->md.max_pages_per_traj);
+    HIPCHECK(hipStreamSynchronize(m->stream));
+    done += k;
+  }
+  return RL_OK;
+}
+
+int take_page(rl_model* m) {
+  int p = m->free_pages.top();
+  m->free_pages.pop();
+  m->refcount[p] = 1;
+  m->n_free--;
+  return p;
+}
+void drop_page(rl_model* m, int p) {
+  if (--m->refcount[p] == 0) {
+    m->free_pages.push(p);
+    m->n_free++;
+  }
+}
+
+int check_ids(const int32_t* ids, int32_t n) {
+  if (n < 0 || (n > 0 && !ids)) return fail(RL_E_ARG, "null ids or negative count");
+  std::unordered_set<int32_t> seen;
+  for (int i = 0; i < n; i++)
+    if (ids[i] < 0) return fail(RL_E_ARG, "negative trajectory id");
+  for (int i = 0; i < n; i++)
+    if (!seen.insert(ids[i]).second) return fail(RL_E_DUP_ID, "duplicate trajectory id");
+  return RL_OK;
+}
+
+// attention work items for `cnt` consecutive rows of one trajectory starting at batch row row0
+void add_items(rl_model* m, Staging& st, int row0, int cnt, int slot, int pos0) {
+  int R = m->rows_per_item;
+  for (int a = 0; a < cnt; a += R)
+    st.items.push_back(AttnItem{row0 + a, std::min(R, cnt - a), slot, pos0 + a});
+}
+
+int pick_attn_splits(rl_model* m, int n_items, int max_pos) {
+  if (!m->mfma || n_items > m->rt.max_trajectories) return 1;
+  int waves = n_items * m->md.nkv * 4;
+  int want = (4096 + waves - 1) / waves;
+  int pages = max_pos / RL_PAGE + 1;
+  int cap = std::max(1, pages / 16);         // at least ~4 pages per wave
+  return std::max(1, std::min({want, cap, m->max_attn_splits}));
+}
+
+// Chunked prefill of tokens[n_cached .. upto) for the listed trajectories (upto given per traj).
+int prefill(rl_model* m, const std::vector<std::pair<Traj*, int>>& work) {
+  Staging st;
+  int cap = m->rt.max_batch_rows;
+  size_t wi = 0;
+  int cur = work.empty() ? 0 : work[0].first->n_cached;
+  while (wi < work.size()) {
+    st.clear();
+    while (wi < work.size() && (int)st.tok.size() < cap) {
+      Traj* t = work[wi].first;
+      int upto = work[wi].second;
+      if (cur >= upto) {
+        t->n_cached = std::max(t->n_cached, upto);
+        wi++;
+        if (wi < work.size()) cur = work[wi].first->n_cached;
+        continue;
+      }
+      int take = std::min(upto - cur, cap - (int)st.tok.size());
+      add_items(m, st, (int)st.tok.size(), take, t->slot, cur);
+      for (int p = cur; p < cur + take; p++) {
+        st.tok.push_back(t->tokens[p]);
+        st.pos.push_back(p);
+        st.slot.push_back(t->slot);
+      }
+      cur += take;
+    }
+    int M = (int)st.tok.size();
+    if (M == 0) break;
+    DevMeta dm;
+    int rc = upload_meta(m, st, &dm);
+    if (rc) return rc;
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), 1, 0.0, false};
+    forward_rows(m, M, r);
+    HIPCHECK(hipGetLastError());
+    HIPCHECK(hipStreamSynchronize(m->stream));
+  }
+  return RL_OK;
+}
+
+int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature, uint64_t seed,
+                  const int32_t* forced, int32_t* ids_out, float* lp_out) {
+  int rc = check_ids(ids, n);
+  if (rc) return rc;
+  if (!(temperature >= 0.0f)) return fail(RL_E_ARG, "negative temperature");
+  if (n > 0 && !lp_out) return fail(RL_E_ARG, "null output");
+  if (n > m->rt.max_trajectories) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  std::vector<Traj*> ts(n);
+  for (int i = 0; i < n; i++) {
+    auto it = m->traj.find(ids[i]);
+    if (it == m->traj.end()) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+    ts[i] = &it->second;
+  }
+  for (Traj* t : ts)
+    if (t->tokens.empty()) return fail(RL_E_EMPTY, "trajectory has no context");
+  if (forced)
+    for (int i = 0; i < n; i++)
+      if (forced[i] < 0 || forced[i] >= m->cfg.vocab) return fail(RL_E_BAD_TOKEN, "forced token out of range");
+  int64_t need = 0;
+  for (Traj* t : ts) {
+    if ((int)t->tokens.size() + 1 > m->rt.max_context) return fail(RL_E_CTX_OVERFLOW, "context overflow");
+    if (t->tokens.size() % RL_PAGE == 0) need++;
+  }
+  if (need > m->n_free) return fail(RL_E_NOPAGES, "page pool exhausted");
+  if (n == 0) return RL_OK;
+  // commit page reservations (call order), then compute
+  std::vector<int32_t> upd;
+  for (Traj* t : ts)
+    if (t->tokens.size() % RL_PAGE == 0) {
+      int p = take_page(m);
+      upd.insert(upd.end(), {t->slot, (int32_t)t->pages.size(), p});
+      t->pages.push_back(p);
+    }
+  if (!upd.empty()) { rc = push_page_updates(m, upd); if (rc) return rc; }
+  Staging st;
+  int max_pos = 0;
+  double kvb = 0.0;
+  for (int i = 0; i < n; i++) {
+    Traj* t = ts[i];
+    int nt = (int)t->tokens.size();
+    st.tok.push_back(t->tokens[nt - 1]);
+    st.pos.push_back(nt - 1);
+    st.slot.push_back(t->slot);
+    st.traj.push_back(ids[i]);
+    st.newpos.push_back(nt);
+    if (forced) st.forced.push_back(forced[i]);
+    st.items.push_back(AttnItem{i, 1, t->slot, nt - 1});
+    max_pos = std::max(max_pos, nt - 1);
+    kvb += (double)nt * 2.0 * m->md.nkv * m->md.d * m->el;
+  }
+  DevMeta dm;
+  rc = upload_meta(m, st, &dm);
+  if (rc) return rc;
+  bool timed = m->timing_every > 0 && (m->decode_steps % m->timing_every) == 0;
+  m->decode_steps++;
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, n, pick_attn_splits(m, n, max_pos), kvb, timed};
+  forward_rows(m, n, r);
+  lm_head_rows(m, n, 0, n, false);
+  bool greedy = temperature == 0.0f;
+  float c = (float)(1.4426950408889634 / (greedy ? 1.0 : (double)temperature));
+  launch_sampler(m->stream, m->logits, (size_t)m->md.V, n, m->md.V, c, greedy ? 1 : 0, nullptr, seed,
+                 dm.traj, dm.newpos, forced ? dm.forced : nullptr, nullptr, m->ss, m->d_ids, m->d_lp);
+  HIPCHECK(hipGetLastError());
+  HIPCHECK(hipMemcpyAsync(m->h_ids, m->d_ids, n * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHECK(hipMemcpyAsync(m->h_lp, m->d_lp, n * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHECK(hipStreamSynchronize(m->stream));
+  if (timed) {
+    for (int l = 0; l < m->md.L; l++) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, m->ev[2 * l], m->ev[2 * l + 1]) == hipSuccess) {
+        m->attn_ms += ms;
+        m->attn_launches++;
+        m->attn_bytes += kvb;
+      }
+    }
+  }
+  for (int i = 0; i < n; i++) {
+    Traj* t = ts[i];
+    t->n_cached = (int)t->tokens.size();
+    t->tokens.push_back(m->h_ids[i]);
+    t->mask.push_back(0);
+    t->logp.push_back(m->h_lp[i]);
+    if (ids_out) ids_out[i] = m->h_ids[i];
+    lp_out[i] = m->h_lp[i];
+  }
+  return RL_OK;
+}
+
+}  // namespace
+
+// =============================================================================================
+extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, size_t nbytes,
+                             rl_model** out) {
+  if (!rt || !weights || !out || nbytes < 64) return fail(RL_E_ARG, "null argument or short blob");
+  const unsigned char* b = (const unsigned char*)weights;
+  uint32_t version;
+  memcpy(&version, b + 4, 4);
+  if (memcmp(b, "RLW1", 4) != 0 || version != 1) return fail(RL_E_ARG, "bad blob magic / version");
+  rl_model_config c;
+  memcpy(&c, b + 8, sizeof(c));
+  if (c.n_layers <= 0 || c.hidden <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 ||
+      c.intermediate <= 0 || c.vocab <= 0 || c.n_q_heads % c.n_kv_heads != 0 || c.head_dim % 2 != 0 ||
+      c.head_dim > 256 || (c.weight_dtype != 0 && c.weight_dtype != 1))
+    return fail(RL_E_ARG, "bad model config");
+  if (c.weight_dtype == 1 && (c.hidden % 16 != 0 || c.intermediate % 16 != 0))
+    return fail(RL_E_ARG, "bf16 models need hidden and intermediate to be multiples of 16");
+  if (rt->page_tokens != RL_PAGE || rt->max_context <= 0 || rt->max_trajectories <= 0 ||
+      rt->kv_pool_pages <= 0 || rt->kv_pool_pages > 0x7fffffff || rt->max_batch_rows < 0)
+    return fail(RL_E_ARG, "bad runtime config");
+  BlobMap bm = map_blob(c);
+  size_t el = c.weight_dtype == 1 ? 2 : 4;
+  if (nbytes != 64 + bm.total * el) return fail(RL_E_ARG, "blob size does not match its header");
+
+  rl_model* m = new rl_model();
+  m->cfg = c;
+  m->rt = *rt;
+  if (m->rt.max_batch_rows == 0) m->rt.max_batch_rows = 8192;
+  m->bf16 = c.weight_dtype == 1;
+  m->el = el;
+  m->mfma = m->bf16 && mfma_shape_ok(c) && !(rt->flags & RL_FLAG_GENERIC_KERNELS);
+  int max_pages = (rt->max_context + RL_PAGE - 1) / RL_PAGE;
+  m->md = ModelDims{c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads, c.head_dim, c.intermediate,
+                    c.vocab, c.rms_eps, c.qk_norm, max_pages};
+  m->rows_per_item = m->mfma ? 16 / (c.n_q_heads / c.n_kv_heads) : 1;
+  int rc = RL_OK;
+#define TRY(x) do { rc = (x); if (rc) { rl_model_free(m); return rc; } } while (0)
+#define HIPTRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fail(RL_E_HIP, std::string(#x) + ": " + hipGetErrorString(e_)); rl_model_free(m); return RL_E_HIP; } } while (0)
+  HIPTRY(hipStreamCreate(&m->stream));
+  // ---- weights ----
+  int H = c.hidden, d = c.head_dim, I = c.intermediate, V = c.vocab;
+  int qw = c.n_q_heads * d, kvw = c.n_kv_heads * d;
+  char* raw = nullptr;  // device copy of the tensor area
+  HIPTRY(hipMalloc((void**)&raw, bm.total * el));
+  hipError_t ce = hipMemcpy(raw, b + 64, bm.total * el, hipMemcpyHostToDevice);
+  if (ce != hipSuccess) { (void)hipFree(raw); fail(RL_E_HIP, "weight upload failed"); rl_model_free(m); return RL_E_HIP; }
+  auto at = [&](size_t off) { return (void*)(raw + off * el); };
+  m->layers.resize(c.n_layers);
+  if (!m->mfma) {
+    m->allocs.push_back(raw);  // keep the blob image, point into it
+    m->embed = at(bm.embed); m->g_final = at(bm.g_final); m->lm_head = at(bm.lm_head);
+    for (int l = 0; l < c.n_layers; l++) {
+      const BlobMap::L& x = bm.layers[l];
+      m->layers[l] = LayerW{at(x.g_in), at(x.w_q), at(x.g_q), at(x.g_k), at(x.w_o), at(x.g_post),
+                            at(x.w_gate), at(x.w_down)};
+    }
+  } else {
+    auto fin = [&](int code) { (void)hipFree(raw); return code; };
+    auto keep = [&](void** dst, size_t off, size_t n) -> int {
+      int r2 = m->dalloc(dst, n * 2);
+      if (r2) return r2;
+      if (hipMemcpyAsync(*dst, at(off), n * 2, hipMemcpyDeviceToDevice, m->stream) != hipSuccess)
+        return fail(RL_E_HIP, "device copy failed");
+      return RL_OK;
+    };
+    auto pack = [&](void** dst, size_t off, size_t off_u, int N, int K, bool il) -> int {
+      int r2 = m->dalloc(dst, (size_t)N * K * 2);
+      if (r2) return r2;
+      launch_repack_weight(m->stream, (const bf16_t*)at(off), (const bf16_t*)at(off_u), (bf16_t*)*dst, N, K, il);
+      return RL_OK;
+    };
+    int r2 = keep(&m->embed, bm.embed, (size_t)V * H);
+    if (!r2) r2 = keep(&m->g_final, bm.g_final, H);
+    if (!r2) r2 = pack(&m->lm_head, bm.lm_head, 0, V, H, false);
+    for (int l = 0; l < c.n_layers && !r2; l++) {
+      const BlobMap::L& x = bm.layers[l];
+      LayerW& w = m->layers[l];
+      r2 = keep(&w.g_in, x.g_in, H);
+      if (!r2) r2 = keep(&w.gq, x.g_q, d);
+      if (!r2) r2 = keep(&w.gk, x.g_k, d);
+      if (!r2) r2 = keep(&w.g_post, x.g_post, H);
+      if (!r2) r2 = pack(&w.wqkv, x.w_q, 0, qw + 2 * kvw, H, false);
+      if (!r2) r2 = pack(&w.wo, x.w_o, 0, H, qw, false);
+      if (!r2) r2 = pack(&w.wgu, x.w_gate, x.w_up, 2 * I, H, true);
+      if (!r2) r2 = pack(&w.wdown, x.w_down, 0, H, I, false);
+    }
+    if (!r2 && (hipStreamSynchronize(m->stream) != hipSuccess || hipGetLastError() != hipSuccess))
+      r2 = fail(RL_E_HIP, "weight repack failed");
+    fin(0);
+    if (r2) { rl_model_free(m); return r2; }
+  }
+  // ---- RoPE table: cos/sin(pos * theta^(-2i/d)), computed in double ----
+  {
+    int half = d / 2;
+    std::vector<float> cs((size_t)rt->max_context * half * 2);
+    for (int i = 0; i < half; i++) {
+      double inv = pow((double)c.rope_theta, -2.0 * i / d);
+      for (int p = 0; p < rt->max_context; p++) {
+        double a = (double)p * inv;
+        cs[((size_t)p * half + i) * 2] = (float)cos(a);
+        cs[((size_t)p * half + i) * 2 + 1] = (float)sin(a);
+      }
+    }
+    TRY(m->dalloc((void**)&m->rope_cs, cs.size() * 4));
+    HIPTRY(hipMemcpy(m->rope_cs, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
+  }
+  // ---- KV pool ----
+  m->page_bytes = (size_t)c.n_kv_heads * RL_PAGE * d * el;
+  m->pools.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; l++) {
+    TRY(m->dalloc(&m->pools[l].k, m->page_bytes * rt->kv_pool_pages, true));
+    TRY(m->dalloc(&m->pools[l].v, m->page_bytes * rt->kv_pool_pages, true));
+  }
+  TRY(m->dalloc((void**)&m->page_table, (size_t)rt->max_trajectories * max_pages * 4, true));
+  m->refcount.assign(rt->kv_pool_pages, 0);
+  for (int p = 0; p < rt->kv_pool_pages; p++) m->free_pages.push(p);
+  m->n_free = rt->kv_pool_pages;
+  for (int s = rt->max_trajectories - 1; s >= 0; s--) m->free_slots.push_back(s);
+  // ---- work buffers ----
+  m->Mcap = round_up(std::max(m->rt.max_batch_rows, rt->max_trajectories), 128);
+  m->Rl = round_up(std::max(rt->max_trajectories, 256), 128);
+  size_t Mc = m->Mcap;
+  size_t ael = m->bf16 ? 2 : 4;
+  TRY(m->dalloc((void**)&m->h, Mc * H * 4, true));
+  TRY(m->dalloc((void**)&m->qkv, Mc * (qw + 2 * kvw) * 4, true));
+  TRY(m->dalloc(&m->xa, Mc * H * ael, true));
+  TRY(m->dalloc(&m->xo, Mc * qw * ael, true));
+  TRY(m->dalloc(&m->xm, Mc * I * ael, true));
+  TRY(m->dalloc(&m->qb, Mc * qw * ael, true));
+  if (!m->mfma) TRY(m->dalloc((void**)&m->gu, Mc * 2 * I * 4, true));
+  TRY(m->dalloc((void**)&m->logits, (size_t)m->Rl * V * 4));
+  if (m->mfma)
+    TRY(m->dalloc((void**)&m->attn_scratch,
+                  (size_t)rt->max_trajectories * c.n_kv_heads * m->max_attn_splits * 16 * 130 * 4));
+  int nseg = sampler_nseg(V);
+  TRY(m->dalloc((void**)&m->ss.segmax, (size_t)m->Rl * nseg * 4));
+  TRY(m->dalloc((void**)&m->ss.segarg, (size_t)m->Rl * nseg * 4));
+  TRY(m->dalloc((void**)&m->ss.segw, (size_t)m->Rl * nseg * 8));
+  TRY(m->dalloc((void**)&m->ss.sege, (size_t)m->Rl * nseg * 4));
+  TRY(m->dalloc((void**)&m->d_ids, (size_t)m->Rl * 4));
+  TRY(m->dalloc((void**)&m->d_lp, (size_t)m->Rl * 4));
+  TRY(m->dalloc((void**)&m->d_mask, Mc));
+  m->meta_ints = 10 * Mc + 3 * 65536;
+  TRY(m->dalloc((void**)&m->d_meta, m->meta_ints * 4));
+  HIPTRY(hipHostMalloc((void**)&m->h_meta, m->meta_ints * 4));
+  HIPTRY(hipHostMalloc((void**)&m->h_ids, (size_t)m->Rl * 4));
+  HIPTRY(hipHostMalloc((void**)&m->h_lp, (size_t)m->Rl * 4));
+  m->ev.resize(2 * c.n_layers);
+  for (auto& e : m->ev) HIPTRY(hipEventCreate(&e));
+  HIPTRY(hipDeviceSynchronize());
+#undef TRY
+#undef HIPTRY
+  *out = m;
+  return RL_OK;
+}
+
+extern "C" void rl_model_free(rl_model* m) {
+  if (!m) return;
+  if (m->stream) (void)hipStreamSynchronize(m->stream);
+  for (void* p : m->allocs) (void)hipFree(p);
+  if (m->h_meta) (void)hipHostFree(m->h_meta);
+  if (m->h_ids) (void)hipHostFree(m->h_ids);
+  if (m->h_lp) (void)hipHostFree(m->h_lp);
+  for (auto e : m->ev) if (e) (void)hipEventDestroy(e);
+  if (m->stream) (void)hipStreamDestroy(m->stream);
+  delete m;
+}
+
+extern "C" int rl_model_get_config(const rl_model* m, rl_model_config* out) {
+  if (!m || !out) return fail(RL_E_ARG, "null argument");
+  *out = m->cfg;
+  return RL_OK;
+}
+
+extern "C" int rl_append_observation(rl_model* m, const int32_t* traj_ids, int32_t n,
+                                     const int32_t* tokens, const int32_t* lens) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  int rc = check_ids(traj_ids, n);
+  if (rc) return rc;
+  if (n > 0 && !lens) return fail(RL_E_ARG, "null lens");
+  int64_t total = 0;
+  for (int i = 0; i < n; i++) {
+    if (lens[i] < 0) return fail(RL_E_ARG, "negative length");
+    total += lens[i];
+  }
+  if (total > 0 && !tokens) return fail(RL_E_ARG, "null tokens");
+  for (int64_t i = 0; i < total; i++)
+    if (tokens[i] < 0 || tokens[i] >= m->cfg.vocab) return fail(RL_E_BAD_TOKEN, "token id out of range");
+  int64_t need = 0;
+  int n_new = 0;
+  for (int i = 0; i < n; i++) {
+    auto it = m->traj.find(traj_ids[i]);
+    int64_t cur = it == m->traj.end() ? 0 : (int64_t)it->second.tokens.size();
+    if (it == m->traj.end()) n_new++;
+    if (cur + lens[i] > m->rt.max_context) return fail(RL_E_CTX_OVERFLOW, "context overflow");
+    need += (cur + lens[i] + RL_PAGE - 1) / RL_PAGE - (cur + RL_PAGE - 1) / RL_PAGE;
+  }
+  if ((int64_t)m->traj.size() + n_new > m->rt.max_trajectories)
+    return fail(RL_E_TOO_MANY, "too many trajectories");
+  if (need > m->n_free) return fail(RL_E_NOPAGES, "page pool exhausted");
+  // commit
+  std::vector<int32_t> upd;
+  std::vector<std::pair<Traj*, int>> work;
+  int64_t off = 0;
+  for (int i = 0; i < n; i++) {
+    Traj& t = m->traj[traj_ids[i]];
+    if (t.slot < 0) {
+      t.slot = m->free_slots.back();
+      m->free_slots.pop_back();
+    }
+    size_t after = t.tokens.size() + lens[i];
+    while (t.pages.size() * RL_PAGE < after) {
+      int p = take_page(m);
+      upd.insert(upd.end(), {t.slot, (int32_t)t.pages.size(), p});
+      t.pages.push_back(p);
+    }
+    t.tokens.insert(t.tokens.end(), tokens + off, tokens + off + lens[i]);
+    t.mask.insert(t.mask.end(), lens[i], (uint8_t)1);
+    t.logp.insert(t.logp.end(), lens[i], 0.0f);
+    off += lens[i];
+  }
+  for (int i = 0; i < n; i++) {   // after all insertions: map references are stable now
+    Traj& t = m->traj[traj_ids[i]];
+    if (!t.tokens.empty()) work.push_back({&t, (int)t.tokens.size() - 1});
+  }
+  if (!upd.empty()) { rc = push_page_updates(m, upd); if (rc) return rc; }
+  return prefill(m, work);
+}
+
+extern "C" int rl_decode_step(rl_model* m, const int32_t* ids, int32_t n, float temperature,
+                              uint64_t rng_seed, int32_t* token_ids_out, float* logprobs_out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (n > 0 && !token_ids_out) return fail(RL_E_ARG, "null output");
+  return decode_common(m, ids, n, temperature, rng_seed, nullptr, token_ids_out, logprobs_out);
+}
+
+extern "C" int rl_decode_step_forced(rl_model* m, const int32_t* ids, int32_t n, float temperature,
+                                     const int32_t* forced_token_ids, float* logprobs_out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (n > 0 && !forced_token_ids) return fail(RL_E_ARG, "null forced ids");
+  return decode_common(m, ids, n, temperature, 0, forced_token_ids, nullptr, logprobs_out);
+}
+
+extern "C" int rl_release(rl_model* m, const int32_t* ids, int32_t n) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  int rc = check_ids(ids, n);
+  if (rc) return rc;
+  for (int i = 0; i < n; i++)
+    if (!m->traj.count(ids[i])) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  for (int i = 0; i < n; i++) {
+    Traj& t = m->traj[ids[i]];
+    for (int p : t.pages) drop_page(m, p);
+    m->free_slots.push_back(t.slot);
+    m->traj.erase(ids[i]);
+  }
+  return RL_OK;
+}
+
+extern "C" int rl_fork(rl_model* m, int32_t src, const int32_t* dst_ids, int32_t n) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  int rc = check_ids(dst_ids, n);
+  if (rc) return rc;
+  auto sit = m->traj.find(src);
+  if (sit == m->traj.end()) return fail(RL_E_BAD_TRAJ, "unknown source trajectory");
+  for (int i = 0; i < n; i++)
+    if (dst_ids[i] == src || m->traj.count(dst_ids[i])) return fail(RL_E_DUP_ID, "destination id already exists");
+  int nt = (int)sit->second.tokens.size();
+  int n_shared = nt > 0 ? (nt - 1) / RL_PAGE : 0;   // pages entirely before the last token
+  int n_own = (int)sit->second.pages.size() - n_shared;
+  if ((int64_t)m->traj.size() + n > m->rt.max_trajectories) return fail(RL_E_TOO_MANY, "too many trajectories");
+  if ((int64_t)n_own * n > m->n_free) return fail(RL_E_NOPAGES, "page pool exhausted");
+  std::vector<int32_t> upd, pairs;
+  m->traj.reserve(m->traj.size() + n);
+  for (int i = 0; i < n; i++) {
+    Traj t = m->traj.find(src)->second;   // copy of tokens / mask / logp / n_cached
+    t.slot = m->free_slots.back();
+    m->free_slots.pop_back();
+    for (int k = 0; k < n_shared; k++) m->refcount[t.pages[k]]++;
+    for (int k = n_shared; k < n_shared + n_own; k++) {
+      int p = take_page(m);
+      pairs.push_back(t.pages[k]);
+      pairs.push_back(p);
+      t.pages[k] = p;
+    }
+    for (size_t k = 0; k < t.pages.size(); k++) upd.insert(upd.end(), {t.slot, (int32_t)k, t.pages[k]});
+    m->traj[dst_ids[i]] = std::move(t);
+  }
+  if (!upd.empty()) { rc = push_page_updates(m, upd); if (rc) return rc; }
+  size_t np = pairs.size() / 2, done = 0, cap = m->meta_ints / 2;
+  while (done < np) {
+    size_t k = std::min(cap, np - done);
+    memcpy(m->h_meta, pairs.data() + 2 * done, k * 8);
+    HIPCHECK(hipMemcpyAsync(m->d_meta, m->h_meta, k * 8, hipMemcpyHostToDevice, m->stream));
+    for (int l = 0; l < m->md.L; l++) launch_copy_pages(m->stream, m->pools[l], m->d_meta, (int)k, m->page_bytes);
+    HIPCHECK(hipGetLastError());
+    HIPCHECK(hipStreamSynchronize(m->stream));
+    done += k;
+  }
+  return RL_OK;
+}
+
+extern "C" int rl_traj_info(rl_model* m, int32_t id, int32_t* n_tokens, int32_t* n_pages) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  auto it = m->traj.find(id);
+  if (it == m->traj.end()) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  if (n_tokens) *n_tokens = (int32_t)it->second.tokens.size();
+  if (n_pages) *n_pages = (int32_t)it->second.pages.size();
+  return RL_OK;
+}
+
+extern "C" int rl_traj_read(rl_model* m, int32_t id, int32_t* tokens, uint8_t* obs_mask,
+                            float* logprobs, int32_t* pages) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  auto it = m->traj.find(id);
+  if (it == m->traj.end()) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  const Traj& t = it->second;
+  if (tokens && !t.tokens.empty()) memcpy(tokens, t.tokens.data(), t.tokens.size() * 4);
+  if (obs_mask && !t.mask.empty()) memcpy(obs_mask, t.mask.data(), t.mask.size());
+  if (logprobs && !t.logp.empty()) memcpy(logprobs, t.logp.data(), t.logp.size() * 4);
+  if (pages && !t.pages.empty()) memcpy(pages, t.pages.data(), t.pages.size() * 4);
+  return RL_OK;
+}
+
+extern "C" int64_t rl_free_pages(const rl_model* m) { return m ? m->n_free : -1; }
+
+extern "C" int rl_debug_logits(rl_model* m, int32_t id, float* logits_out) {
+  if (!m || !logits_out) return fail(RL_E_ARG, "null argument");
+  auto it = m->traj.find(id);
+  if (it == m->traj.end()) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  Traj& t = it->second;
+  if (t.tokens.empty()) return fail(RL_E_EMPTY, "trajectory has no context");
+  int nt = (int)t.tokens.size();
+  Staging st;
+  st.tok.push_back(t.tokens[nt - 1]);
+  st.pos.push_back(nt - 1);
+  st.slot.push_back(t.slot);
+  st.items.push_back(AttnItem{0, 1, t.slot, nt - 1});
+  DevMeta dm;
+  int rc = upload_meta(m, st, &dm);
+  if (rc) return rc;
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, 1, pick_attn_splits(m, 1, nt - 1), 0.0, false};
+  forward_rows(m, 1, r);   // rewrites the key / value of position nt-1 with the same values
+  lm_head_rows(m, 1, 0, 1, false);
+  HIPCHECK(hipGetLastError());
+  HIPCHECK(hipMemcpyAsync(logits_out, m->logits, (size_t)m->md.V * 4, hipMemcpyDeviceToHost, m->stream));
+  HIPCHECK(hipStreamSynchronize(m->stream));
+  return RL_OK;
+}
+
+extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n, float temperature,
+                                     float* out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  int rc = check_ids(ids, n);
+  if (rc) return rc;
+  if (!(temperature >= 0.0f) || (n > 0 && !out)) return fail(RL_E_ARG, "bad temperature or null output");
+  for (int i = 0; i < n; i++)
+    if (!m->traj.count(ids[i])) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  float c = (float)(1.4426950408889634 / (temperature == 0.0f ? 1.0 : (double)temperature));
+  // flat list of rows: (trajectory, position p) for p in [0, n_tokens - 1); row p predicts token p+1
+  struct Seg { Traj* t; size_t out_off; };
+  std::vector<Seg> segs;
+  size_t off = 0;
+  for (int i = 0; i < n; i++) {
+    Traj& t = m->traj[ids[i]];
+    segs.push_back({&t, off});
+    for (size_t k = 0; k < t.tokens.size(); k++) out[off + k] = 0.0f;
+    off += t.tokens.size();
+  }
+  Staging st;
+  std::vector<size_t> dest;   // output index of each row's log-prob
+  size_t si = 0;
+  int cur = 0;
+  int cap = m->Mcap;
+  while (si < segs.size()) {
+    st.clear();
+    dest.clear();
+    while (si < segs.size() && (int)st.tok.size() < cap) {
+      Traj* t = segs[si].t;
+      int upto = (int)t->tokens.size() - 1;
+      if (cur >= upto) { si++; cur = 0; continue; }
+      int take = std::min(upto - cur, cap - (int)st.tok.size());
+      add_items(m, st, (int)st.tok.size(), take, t->slot, cur);
+      for (int p = cur; p < cur + take; p++) {
+        st.tok.push_back(t->tokens[p]);
+        st.pos.push_back(p);
+        st.slot.push_back(t->slot);
+        st.forced.push_back(t->tokens[p + 1]);
+        st.mask.push_back(t->mask[p + 1]);
+        dest.push_back(segs[si].out_off + p + 1);
+      }
+      cur += take;
+    }
+    int M = (int)st.tok.size();
+    if (M == 0) break;
+    st.traj.assign(M, 0);
+    st.newpos.assign(M, 0);
+    DevMeta dm;
+    rc = upload_meta(m, st, &dm);
+    if (rc) return rc;
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), 1, 0.0, false};
+    forward_rows(m, M, r);
+    for (int r0 = 0; r0 < M; r0 += m->Rl) {
+      int R = std::min(m->Rl, M - r0);
+      lm_head_rows(m, M, r0, R, r0 > 0);
+      launch_sampler(m->stream, m->logits, (size_t)m->md.V, R, m->md.V, c, 0, nullptr, 0, nullptr,
+                     nullptr, dm.forced + r0, m->d_mask + r0, m->ss, nullptr, m->d_lp);
+      HIPCHECK(hipGetLastError());
+      HIPCHECK(hipMemcpyAsync(m->h_lp, m->d_lp, (size_t)R * 4, hipMemcpyDeviceToHost, m->stream));
+      HIPCHECK(hipStreamSynchronize(m->stream));
+      for (int k = 0; k < R; k++) out[dest[r0 + k]] = m->h_lp[k];
+    }
+  }
+  return RL_OK;
+}
+
+extern "C" int rl_sample_from_logits(const float* logits, int32_t rows, int32_t vocab,
+                                     float temperature, const uint32_t* u32, int32_t* ids_out,
+                                     float* logprobs_out) {
+  if (!logits || !u32 || !ids_out || !logprobs_out || rows <= 0 || vocab <= 0 || !(temperature >= 0.0f))
+    return fail(RL_E_ARG, "bad argument");
+  int nseg = sampler_nseg(vocab);
+  size_t zb = (size_t)rows * vocab * 4;
+  char* buf = nullptr;
+  size_t seg_n = (size_t)rows * nseg;
+  size_t total = zb + seg_n * (4 + 4 + 8 + 4) + (size_t)rows * 12 + 64;
+  HIPCHECK(hipMalloc((void**)&buf, total));
+  float* dz = (float*)buf;
+  SamplerScratch sc;
+  sc.segw = (uint64_t*)(buf + ((zb + 7) / 8) * 8);
+  sc.segmax = (float*)(sc.segw + seg_n);
+  sc.segarg = (int32_t*)(sc.segmax + seg_n);
+  sc.sege = (float*)(sc.segarg + seg_n);
+  uint32_t* du = (uint32_t*)(sc.sege + seg_n);
+  int32_t* dids = (int32_t*)(du + rows);
+  float* dlp = (float*)(dids + rows);
+  int rc = RL_OK;
+  bool greedy = temperature == 0.0f;
+  float c = (float)(1.4426950408889634 / (greedy ? 1.0 : (double)temperature));
+  hipError_t e = hipMemcpy(dz, logits, zb, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(du, u32, (size_t)rows * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) {
+    launch_sampler(nullptr, dz, (size_t)vocab, rows, vocab, c, greedy ? 1 : 0, du, 0, nullptr, nullptr,
+                   nullptr, nullptr, sc, dids, dlp);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpy(ids_out, dids, (size_t)rows * 4, hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemcpy(logprobs_out, dlp, (size_t)rows * 4, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) rc = fail(RL_E_HIP, hipGetErrorString(e));
+  (void)hipFree(buf);
+  return rc;
+}
+
+extern "C" int rl_timing_enable(rl_model* m, int32_t every) {
+  if (!m || every < 0) return fail(RL_E_ARG, "bad argument");
+  m->timing_every = every;
+  return RL_OK;
+}
+
+extern "C" int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches,
+                              double* attn_kv_bytes, int reset) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (attn_ms) *attn_ms = m->attn_ms;
+  if (attn_launches) *attn_launches = m->attn_launches;
+  if (attn_kv_bytes) *attn_kv_bytes = m->attn_bytes;
+  if (reset) { m->attn_ms = 0.0; m->attn_launches = 0; m->attn_bytes = 0.0; }
+  return RL_OK;
+}

@@ -1,0 +1,102 @@
+// Host-side launchers of the rollout kernels.  All pointers are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rl_common.h"
+
+// One attention work item: up to 4 consecutive batch rows of one trajectory that share a
+// pass over its cached context (decode: one row; chunked prefill: 4 rows).
+struct AttnItem {
+  int32_t row0;   // first batch row
+  int32_t nrows;  // 1..4
+  int32_t slot;   // trajectory slot (row of the page table)
+  int32_t pos0;   // position of row0; row r sits at pos0 + r and sees positions <= pos0 + r
+};
+
+struct KvPool {      // one layer
+  void* k;           // [pages][n_kv][16 * d] elements
+  void* v;
+};
+
+struct ModelDims {
+  int L, H, nq, nkv, d, I, V;
+  float eps;
+  int qk_norm;
+  int max_pages_per_traj;  // row stride of the page table
+};
+
+// ---- generic kernels (TA: activation type, TW: weight type; float or bf16_t) -------------
+template <typename TW>
+void launch_embed(hipStream_t s, const TW* E, const int32_t* tok, float* h, int M, int H);
+
+// out = rmsnorm(h) * g.  ATILE: write `out` in A-tile layout (bf16 MFMA path).
+template <typename TW, typename TA>
+void launch_rmsnorm(hipStream_t s, const float* h, const TW* g, TA* out, int M, int H, float eps,
+                    bool atile);
+
+// C[M,N] (+)= A[M,K] * W[N,K]^T, fp32 accumulate, C row-major fp32.
+template <typename TA, typename TW>
+void launch_gemm_generic(hipStream_t s, const TA* A, const TW* W, float* C, int M, int N, int K,
+                         bool accumulate);
+
+// q/k per-head RMSNorm (optional), rotate-half RoPE, q -> qout [M, nq*d] row-major, k and v into
+// the paged cache at (page_table[slot][pos/16], pos%16).  zero_qkv: clear qkv afterwards.
+template <typename TW, typename TA, typename TKV, bool SWZ>
+void launch_qkrope(hipStream_t s, float* qkv, const TW* gq, const TW* gk, const float* rope_cs,
+                   const int32_t* row_pos, const int32_t* row_slot, const int32_t* page_table,
+                   TA* qout, KvPool pool, const ModelDims& md, int M, bool zero_qkv);
+
+template <typename TA, typename TKV, bool SWZ>
+void launch_attention_generic(hipStream_t s, const TA* q, KvPool pool, const int32_t* row_pos,
+                              const int32_t* row_slot, const int32_t* page_table, TA* o,
+                              const ModelDims& md, int M, bool o_atile);
+
+// m = silu(gu[:, :I]) * gu[:, I:]
+template <typename TA>
+void launch_swiglu(hipStream_t s, const float* gu, TA* m, int M, int I, bool atile);
+
+// ---- MFMA kernels (bf16, head_dim 128) -------------------------------------------------------
+enum GemmEpilogue { EPI_STORE = 0, EPI_ATOMIC_ADD = 1, EPI_SWIGLU = 2 };
+// A: bf16 A-tile layout [ceil(M/128)*128, K]; Wp: weights in 32-column operand strips
+// (see repack kernels); C: fp32 row-major [M, N] (EPI_STORE / EPI_ATOMIC_ADD) or bf16 A-tile
+// [.., N/2] (EPI_SWIGLU, gate/up interleaved in 16-column groups).  K % 64 == 0, N % 32 == 0.
+void launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
+                      int K, int epilogue, int splits);
+// W[N,K] row-major -> operand strips.  interleave16: rows come from two matrices Wg, Wu
+// ([N/2,K] each) interleaved in groups of 16 (gate, up, gate, up, ...).
+void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16_t* Wp, int N,
+                          int K, bool interleave16);
+
+// paged GQA attention over work items; q bf16 row-major [M, nq*128]; o bf16 A-tile [.., nq*128].
+// scratch: fp32 [n_items * nkv * splits * 16 * 130] when splits > 1.
+void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
+                           int n_items, const int32_t* page_table, bf16_t* o, float* scratch,
+                           const ModelDims& md, int splits);
+
+// ---- sampler ---------------------------------------------------------------------------------
+struct SamplerScratch {
+  float* segmax;     // [rows * nseg]
+  int32_t* segarg;   // [rows * nseg]
+  uint64_t* segw;    // [rows * nseg]
+  float* sege;       // [rows * nseg]
+};
+#define RL_SAMPLER_SEG 4096
+static inline int sampler_nseg(int V) { return (V + RL_SAMPLER_SEG - 1) / RL_SAMPLER_SEG; }
+
+// For each row of fp32 logits [rows, V] (row stride ldz): id and log-prob.
+//  scale_c = fl32(log2(e)/T) (T > 0) or fl32(log2(e)) with greedy = 1.
+//  u32 != null: use these draws; else draw from (seed, row_traj[r], row_newpos[r]).
+//  forced != null: id = forced[r] (no draw).  out_mask != null: logprob forced to 0 where
+//  out_mask[r] != 0.
+void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, int V, float scale_c,
+                    int greedy, const uint32_t* u32, uint64_t seed, const int32_t* row_traj,
+                    const int32_t* row_newpos, const int32_t* forced, const uint8_t* out_mask,
+                    SamplerScratch sc, int32_t* ids_out, float* logp_out);
+
+// copy one page (all kv heads) within a layer pool: dst page <- src page; n pairs
+void launch_copy_pages(hipStream_t s, KvPool pool, const int32_t* src_dst_pairs, int n_pairs,
+                       size_t page_bytes);
+// page_table[upd[3i] * stride + upd[3i+1]] = upd[3i+2]
+void launch_page_table_update(hipStream_t s, int32_t* page_table, const int32_t* upd, int n,
+                              int stride);

@@ -1,0 +1,294 @@
+// Shape-generic kernels: fp32 mode, and bf16 models whose shape the MFMA kernels do not cover.
+// One decoder block of the policy pi_theta(a | s_t) (paper Section 2.2) is
+//   h += W_o attn(rope(norm(W_q a)), rope(norm(W_k a)), W_v a),  a = rmsnorm(h)
+//   h += W_down (silu(W_gate b) * W_up b),                       b = rmsnorm(h)
+// Each kernel below is one of those pieces; accumulation is always fp32.
+#include "kernels.h"
+
+template <typename TW>
+__global__ void embed_kernel(const TW* __restrict__ E, const int32_t* __restrict__ tok,
+                             float* __restrict__ h, int H) {
+  int row = blockIdx.x;
+  const TW* e = E + (size_t)tok[row] * H;
+  for (int j = threadIdx.x; j < H; j += blockDim.x) h[(size_t)row * H + j] = ldf(e + j);
+}
+
+template <typename TW, typename TA, bool ATILE>
+__global__ void rmsnorm_kernel(const float* __restrict__ h, const TW* __restrict__ g,
+                               TA* __restrict__ out, int H, float eps) {
+  __shared__ float red[4];
+  int row = blockIdx.x;
+  const float* x = h + (size_t)row * H;
+  float ss = 0.f;
+  for (int j = threadIdx.x; j < H; j += 256) ss += x[j] * x[j];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = red[0] + red[1] + red[2] + red[3];
+  float inv = 1.0f / sqrtf(tot / (float)H + eps);
+  for (int j = threadIdx.x; j < H; j += 256) {
+    float y = x[j] * inv * ldf(g + j);
+    if (ATILE) stf(out + atile_off(row, j, H), y);
+    else stf(out + (size_t)row * H + j, y);
+  }
+}
+
+template <typename TA, typename TW>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const TA* __restrict__ A,
+                                                           const TW* __restrict__ W,
+                                                           float* __restrict__ C, int M, int N,
+                                                           int K, int accumulate) {
+  __shared__ float As[16][65];
+  __shared__ float Ws[16][65];
+  int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      int e = tid + i * 256, r = e >> 4, kk = e & 15;
+      int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
+      As[kk][r] = (gm < M && gk < K) ? ldf(A + (size_t)gm * K + gk) : 0.f;
+      Ws[kk][r] = (gn < N && gk < K) ? ldf(W + (size_t)gn * K + gk) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; i++) { a[i] = As[kk][ty * 4 + i]; b[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) acc[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      int gm = m0 + ty * 4 + i, gn = n0 + tx * 4 + j;
+      if (gm < M && gn < N) {
+        float* c = C + (size_t)gm * N + gn;
+        *c = accumulate ? *c + acc[i][j] : acc[i][j];
+      }
+    }
+}
+
+// grid (M, nq + 2 nkv), block 64
+template <typename TW, typename TA, typename TKV, bool SWZ>
+__global__ void qkrope_kernel(float* __restrict__ qkv, const TW* __restrict__ gq,
+                              const TW* __restrict__ gk, const float* __restrict__ rope_cs,
+                              const int32_t* __restrict__ row_pos,
+                              const int32_t* __restrict__ row_slot,
+                              const int32_t* __restrict__ page_table, TA* __restrict__ qout,
+                              TKV* __restrict__ kpool, TKV* __restrict__ vpool, int nq, int nkv,
+                              int d, float eps, int qk_norm, int pt_stride, int zero_qkv) {
+  int row = blockIdx.x, hd = blockIdx.y, half = d >> 1;
+  int pos = row_pos[row];
+  float* x = qkv + (size_t)row * (nq + 2 * nkv) * d + (size_t)hd * d;
+  bool is_q = hd < nq, is_v = hd >= nq + nkv;
+  float x1[2], x2[2];
+  float ss = 0.f;
+  int cnt = 0;
+  for (int i = threadIdx.x; i < half; i += 64, cnt++) {
+    x1[cnt] = x[i];
+    x2[cnt] = x[i + half];
+    ss += x1[cnt] * x1[cnt] + x2[cnt] * x2[cnt];
+    if (zero_qkv) { x[i] = 0.f; x[i + half] = 0.f; }
+  }
+  ss = wave_sum(ss);
+  float inv = (qk_norm && !is_v) ? 1.0f / sqrtf(ss / (float)d + eps) : 1.0f;
+  TKV* blk = nullptr;
+  int tok = pos & (RL_PAGE - 1);
+  if (!is_q) {
+    int page = page_table[(size_t)row_slot[row] * pt_stride + (pos >> 4)];
+    int kvh = is_v ? hd - nq - nkv : hd - nq;
+    blk = (is_v ? vpool : kpool) + ((size_t)page * nkv + kvh) * (RL_PAGE * d);
+  }
+  const TW* g = is_q ? gq : gk;
+  cnt = 0;
+  for (int i = threadIdx.x; i < half; i += 64, cnt++) {
+    float a = x1[cnt], b = x2[cnt];
+    if (is_v) {
+      stf(blk + vblk_off<SWZ>(tok, i, d), a);
+      stf(blk + vblk_off<SWZ>(tok, i + half, d), b);
+      continue;
+    }
+    if (qk_norm) { a = a * inv * ldf(g + i); b = b * inv * ldf(g + i + half); }
+    float c = rope_cs[((size_t)pos * half + i) * 2], s = rope_cs[((size_t)pos * half + i) * 2 + 1];
+    float y1 = a * c - b * s, y2 = b * c + a * s;
+    if (is_q) {
+      stf(qout + (size_t)row * nq * d + (size_t)hd * d + i, y1);
+      stf(qout + (size_t)row * nq * d + (size_t)hd * d + i + half, y2);
+    } else {
+      stf(blk + kblk_off<SWZ>(tok, i, d), y1);
+      stf(blk + kblk_off<SWZ>(tok, i + half, d), y2);
+    }
+  }
+}
+
+// grid (M, nq), block 64: one wave per (row, q head); tokens in blocks of 64, online softmax
+template <typename TA, typename TKV, bool SWZ, bool OATILE>
+__global__ void attention_generic_kernel(const TA* __restrict__ q, const TKV* __restrict__ kpool,
+                                         const TKV* __restrict__ vpool,
+                                         const int32_t* __restrict__ row_pos,
+                                         const int32_t* __restrict__ row_slot,
+                                         const int32_t* __restrict__ page_table,
+                                         TA* __restrict__ o, int nq, int nkv, int d,
+                                         int pt_stride) {
+  __shared__ float qs[128];
+  __shared__ float ps[64];
+  int row = blockIdx.x, qh = blockIdx.y, kvh = qh / (nq / nkv);
+  int pos = row_pos[row];
+  const int32_t* pt = page_table + (size_t)row_slot[row] * pt_stride;
+  for (int e = threadIdx.x; e < d; e += 64) qs[e] = ldf(q + (size_t)row * nq * d + (size_t)qh * d + e);
+  __syncthreads();
+  float scale = 1.0f / sqrtf((float)d);
+  float m = -INFINITY, l = 0.f, acc[2] = {0.f, 0.f};
+  for (int t0 = 0; t0 <= pos; t0 += 64) {
+    int t = t0 + threadIdx.x;
+    float sc = -INFINITY;
+    if (t <= pos) {
+      const TKV* kb = kpool + ((size_t)pt[t >> 4] * nkv + kvh) * (RL_PAGE * d);
+      float dot = 0.f;
+      for (int e = 0; e < d; e++) dot += qs[e] * ldf(kb + kblk_off<SWZ>(t & 15, e, d));
+      sc = dot * scale;
+    }
+    float mn = fmaxf(m, wave_max(sc));
+    float p = (t <= pos) ? expf(sc - mn) : 0.f;
+    float alpha = expf(m - mn);       // m = -inf on the first block: exp(-inf) = 0
+    l = l * alpha + wave_sum(p);
+    m = mn;
+    __syncthreads();
+    ps[threadIdx.x] = p;
+    __syncthreads();
+    int nt = min(64, pos + 1 - t0);
+    int c = 0;
+    for (int e = threadIdx.x; e < d; e += 64, c++) {
+      float a = acc[c] * alpha;
+      for (int j = 0; j < nt; j++) {
+        int tt = t0 + j;
+        const TKV* vb = vpool + ((size_t)pt[tt >> 4] * nkv + kvh) * (RL_PAGE * d);
+        a += ps[j] * ldf(vb + vblk_off<SWZ>(tt & 15, e, d));
+      }
+      acc[c] = a;
+    }
+  }
+  int c = 0;
+  for (int e = threadIdx.x; e < d; e += 64, c++) {
+    float y = acc[c] / l;
+    if (OATILE) stf(o + atile_off(row, qh * d + e, nq * d), y);
+    else stf(o + (size_t)row * nq * d + (size_t)qh * d + e, y);
+  }
+}
+
+template <typename TA, bool ATILE>
+__global__ void swiglu_kernel(const float* __restrict__ gu, TA* __restrict__ m, int I) {
+  int row = blockIdx.y;
+  int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= I) return;
+  float g = gu[(size_t)row * 2 * I + j], u = gu[(size_t)row * 2 * I + I + j];
+  float y = g / (1.0f + expf(-g)) * u;
+  if (ATILE) stf(m + atile_off(row, j, I), y);
+  else stf(m + (size_t)row * I + j, y);
+}
+
+__global__ void copy_pages_kernel(char* __restrict__ k, char* __restrict__ v,
+                                  const int32_t* __restrict__ pairs, size_t page_bytes) {
+  int p = blockIdx.x;
+  size_t src = (size_t)pairs[2 * p] * page_bytes, dst = (size_t)pairs[2 * p + 1] * page_bytes;
+  char* base = blockIdx.y ? v : k;
+  const uint4* s4 = (const uint4*)(base + src);
+  uint4* d4 = (uint4*)(base + dst);
+  for (size_t i = threadIdx.x; i < page_bytes / 16; i += blockDim.x) d4[i] = s4[i];
+}
+
+__global__ void page_table_update_kernel(int32_t* __restrict__ pt, const int32_t* __restrict__ upd,
+                                         int n, int stride) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) pt[(size_t)upd[3 * i] * stride + upd[3 * i + 1]] = upd[3 * i + 2];
+}
+
+// ---- launchers ---------------------------------------------------------------------------
+template <typename TW>
+void launch_embed(hipStream_t s, const TW* E, const int32_t* tok, float* h, int M, int H) {
+  if (M > 0) embed_kernel<TW><<<M, 256, 0, s>>>(E, tok, h, H);
+}
+template void launch_embed<float>(hipStream_t, const float*, const int32_t*, float*, int, int);
+template void launch_embed<bf16_t>(hipStream_t, const bf16_t*, const int32_t*, float*, int, int);
+
+template <typename TW, typename TA>
+void launch_rmsnorm(hipStream_t s, const float* h, const TW* g, TA* out, int M, int H, float eps,
+                    bool atile) {
+  if (M <= 0) return;
+  if (atile) rmsnorm_kernel<TW, TA, true><<<M, 256, 0, s>>>(h, g, out, H, eps);
+  else rmsnorm_kernel<TW, TA, false><<<M, 256, 0, s>>>(h, g, out, H, eps);
+}
+template void launch_rmsnorm<float, float>(hipStream_t, const float*, const float*, float*, int, int, float, bool);
+template void launch_rmsnorm<bf16_t, bf16_t>(hipStream_t, const float*, const bf16_t*, bf16_t*, int, int, float, bool);
+
+template <typename TA, typename TW>
+void launch_gemm_generic(hipStream_t s, const TA* A, const TW* W, float* C, int M, int N, int K,
+                         bool accumulate) {
+  if (M <= 0) return;
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  gemm_generic_kernel<TA, TW><<<grid, 256, 0, s>>>(A, W, C, M, N, K, accumulate ? 1 : 0);
+}
+template void launch_gemm_generic<float, float>(hipStream_t, const float*, const float*, float*, int, int, int, bool);
+template void launch_gemm_generic<bf16_t, bf16_t>(hipStream_t, const bf16_t*, const bf16_t*, float*, int, int, int, bool);
+
+template <typename TW, typename TA, typename TKV, bool SWZ>
+void launch_qkrope(hipStream_t s, float* qkv, const TW* gq, const TW* gk, const float* rope_cs,
+                   const int32_t* row_pos, const int32_t* row_slot, const int32_t* page_table,
+                   TA* qout, KvPool pool, const ModelDims& md, int M, bool zero_qkv) {
+  if (M <= 0) return;
+  dim3 grid(M, md.nq + 2 * md.nkv);
+  qkrope_kernel<TW, TA, TKV, SWZ><<<grid, 64, 0, s>>>(
+      qkv, gq, gk, rope_cs, row_pos, row_slot, page_table, qout, (TKV*)pool.k, (TKV*)pool.v, md.nq,
+      md.nkv, md.d, md.eps, md.qk_norm, md.max_pages_per_traj, zero_qkv ? 1 : 0);
+}
+template void launch_qkrope<float, float, float, false>(hipStream_t, float*, const float*, const float*, const float*, const int32_t*, const int32_t*, const int32_t*, float*, KvPool, const ModelDims&, int, bool);
+template void launch_qkrope<bf16_t, bf16_t, bf16_t, false>(hipStream_t, float*, const bf16_t*, const bf16_t*, const float*, const int32_t*, const int32_t*, const int32_t*, bf16_t*, KvPool, const ModelDims&, int, bool);
+template void launch_qkrope<bf16_t, bf16_t, bf16_t, true>(hipStream_t, float*, const bf16_t*, const bf16_t*, const float*, const int32_t*, const int32_t*, const int32_t*, bf16_t*, KvPool, const ModelDims&, int, bool);
+
+template <typename TA, typename TKV, bool SWZ>
+void launch_attention_generic(hipStream_t s, const TA* q, KvPool pool, const int32_t* row_pos,
+                              const int32_t* row_slot, const int32_t* page_table, TA* o,
+                              const ModelDims& md, int M, bool o_atile) {
+  if (M <= 0) return;
+  dim3 grid(M, md.nq);
+  if (o_atile)
+    attention_generic_kernel<TA, TKV, SWZ, true><<<grid, 64, 0, s>>>(
+        q, (const TKV*)pool.k, (const TKV*)pool.v, row_pos, row_slot, page_table, o, md.nq, md.nkv,
+        md.d, md.max_pages_per_traj);
+  else
+    attention_generic_kernel<TA, TKV, SWZ, false><<<grid, 64, 0, s>>>(
+        q, (const TKV*)pool.k, (const TKV*)pool.v, row_pos, row_slot, page_table, o, md.nq, md.nkv,
+        md.d, md.max_pages_per_traj);
+}
+template void launch_attention_generic<float, float, false>(hipStream_t, const float*, KvPool, const int32_t*, const int32_t*, const int32_t*, float*, const ModelDims&, int, bool);
+template void launch_attention_generic<bf16_t, bf16_t, false>(hipStream_t, const bf16_t*, KvPool, const int32_t*, const int32_t*, const int32_t*, bf16_t*, const ModelDims&, int, bool);
+template void launch_attention_generic<bf16_t, bf16_t, true>(hipStream_t, const bf16_t*, KvPool, const int32_t*, const int32_t*, const int32_t*, bf16_t*, const ModelDims&, int, bool);
+
+template <typename TA>
+void launch_swiglu(hipStream_t s, const float* gu, TA* m, int M, int I, bool atile) {
+  if (M <= 0) return;
+  dim3 grid((I + 255) / 256, M);
+  if (atile) swiglu_kernel<TA, true><<<grid, 256, 0, s>>>(gu, m, I);
+  else swiglu_kernel<TA, false><<<grid, 256, 0, s>>>(gu, m, I);
+}
+template void launch_swiglu<float>(hipStream_t, const float*, float*, int, int, bool);
+template void launch_swiglu<bf16_t>(hipStream_t, const float*, bf16_t*, int, int, bool);
+
+void launch_copy_pages(hipStream_t s, KvPool pool, const int32_t* pairs, int n_pairs,
+                       size_t page_bytes) {
+  if (n_pairs <= 0) return;
+  copy_pages_kernel<<<dim3(n_pairs, 2), 256, 0, s>>>((char*)pool.k, (char*)pool.v, pairs, page_bytes);
+}
+void launch_page_table_update(hipStream_t s, int32_t* page_table, const int32_t* upd, int n,
+                              int stride) {
+  if (n <= 0) return;
+  page_table_update_kernel<<<(n + 255) / 256, 256, 0, s>>>(page_table, upd, n, stride);
+}

@@ -1,0 +1,342 @@
+// bf16 MFMA kernels for gfx950: weight-streaming GEMM, weight repack, paged GQA attention.
+// They implement the same decoder pieces as the generic kernels (policy forward of the paper's
+// Generate / Update steps, Section 2.3.2) for head_dim 128 and tile-aligned widths.
+#include "kernels.h"
+
+// =============================================================================================
+// Weight repack: W[N,K] row-major -> strips of 32 output columns; inside a strip, one 1 KB block
+// per 16 k holds a 32x32x16 MFMA column operand in lane order
+// (lane = n % 32 + 32 * ((k % 16) / 8), 8 consecutive k per lane).  A wave streaming its strip
+// reads one contiguous run of K * 64 bytes.
+// =============================================================================================
+__global__ void repack_weight_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ Wu,
+                                     bf16_t* __restrict__ Wp, int N, int K, int interleave16) {
+  size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)(N / 32) * (K / 16) * 64;
+  if (t >= total) return;
+  int lane = (int)(t & 63);
+  size_t blk = t >> 6;
+  int kb = (int)(blk % (K / 16));
+  int nb = (int)(blk / (K / 16));
+  int n = nb * 32 + (lane & 31);
+  int k = kb * 16 + (lane >> 5) * 8;
+  const bf16_t* src;
+  if (interleave16) {
+    int grp = n >> 4;                       // even groups: gate rows, odd groups: up rows
+    int srow = (grp >> 1) * 16 + (n & 15);
+    src = ((grp & 1) ? Wu : W) + (size_t)srow * K + k;
+  } else {
+    src = W + (size_t)n * K + k;
+  }
+  *(uint4*)(Wp + t * 8) = *(const uint4*)src;
+}
+
+void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16_t* Wp, int N,
+                          int K, bool interleave16) {
+  size_t total = (size_t)(N / 32) * (K / 16) * 64;
+  repack_weight_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(W, Wu, Wp, N, K,
+                                                                        interleave16 ? 1 : 0);
+}
+
+// =============================================================================================
+// GEMM  C[M,N] = A[M,K] * W[N,K]^T.  Workgroup = 4 waves, tile 128 rows x 128 columns; wave w owns
+// the 32-column strip 4*blockIdx.x + w for all 128 rows (4 accumulators of 32x32).  Per 64-k chunk
+// the A tile (16 KB, already in operand order in HBM) is copied to LDS and shared by the waves;
+// each wave streams its own weight strip straight from HBM into registers, one chunk ahead.
+// blockIdx.z selects a K-slice (split-K, results combined with fp32 atomics).
+// =============================================================================================
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
+                                                        const bf16_t* __restrict__ Wp,
+                                                        void* __restrict__ Cv, int M, int N, int K,
+                                                        int chunks_per_split) {
+  __shared__ uint4 As[1024];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int nb = blockIdx.x * 4 + wave;
+  const bool active = nb * 32 < N;
+  const int mt = blockIdx.y;
+  const int nchunks = K >> 6;
+  const int c0 = blockIdx.z * chunks_per_split;
+  const int c1 = min(c0 + chunks_per_split, nchunks);
+  const uint4* Ag = (const uint4*)(A + (size_t)mt * K * 128);       // tile: 128 rows x K
+  const uint4* Wg = (const uint4*)(Wp + (size_t)nb * K * 32);       // strip: 32 columns x K
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 16; j++) acc[i][j] = 0.f;
+  uint4 areg[4], bnext[4], bcur[4];
+  if (c0 < c1) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) areg[i] = Ag[(size_t)c0 * 1024 + i * 256 + tid];
+    if (active) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) bnext[i] = Wg[(size_t)(c0 * 4 + i) * 64 + lane];
+    }
+  }
+  for (int c = c0; c < c1; c++) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; i++) { As[i * 256 + tid] = areg[i]; bcur[i] = bnext[i]; }
+    __syncthreads();
+    if (c + 1 < c1) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) areg[i] = Ag[(size_t)(c + 1) * 1024 + i * 256 + tid];
+      if (active) {
+#pragma unroll
+        for (int i = 0; i < 4; i++) bnext[i] = Wg[(size_t)((c + 1) * 4 + i) * 64 + lane];
+      }
+    }
+    if (active) {
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++) {
+        bf16x8 b = __builtin_bit_cast(bf16x8, bcur[kk]);
+#pragma unroll
+        for (int mb = 0; mb < 4; mb++) {
+          bf16x8 a = __builtin_bit_cast(bf16x8, As[(kk * 4 + mb) * 64 + lane]);
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (!active) return;
+  const int col = nb * 32 + (lane & 31);
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++) {
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      int row = mt * 128 + mb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+      float v = acc[mb][i];
+      if (EPI == EPI_SWIGLU) {
+        float u = __shfl_xor(v, 16, 64);            // lanes 0..15 of a half: gate; 16..31: up
+        if ((lane & 16) == 0 && row < M) {
+          float y = v / (1.0f + __expf(-v)) * u;
+          int j = nb * 16 + (lane & 15);
+          ((bf16_t*)Cv)[atile_off(row, j, N >> 1)] = f2bf(y);
+        }
+      } else if (row < M) {
+        float* c = (float*)Cv + (size_t)row * N + col;
+        if (EPI == EPI_ATOMIC_ADD) unsafeAtomicAdd(c, v);
+        else *c = v;
+      }
+    }
+  }
+}
+
+void launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
+                      int K, int epilogue, int splits) {
+  if (M <= 0) return;
+  int nchunks = K / 64;
+  if (splits < 1) splits = 1;
+  if (splits > nchunks) splits = nchunks;
+  int cps = (nchunks + splits - 1) / splits;
+  splits = (nchunks + cps - 1) / cps;
+  dim3 grid((N + 127) / 128, (M + 127) / 128, splits);
+  if (epilogue == EPI_STORE)
+    gemm_mfma_kernel<EPI_STORE><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+  else if (epilogue == EPI_ATOMIC_ADD)
+    gemm_mfma_kernel<EPI_ATOMIC_ADD><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+  else
+    gemm_mfma_kernel<EPI_SWIGLU><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+}
+
+// =============================================================================================
+// Paged GQA attention, one workgroup (4 waves) per (work item, kv head, context split).
+// The MFMA column index n = G * r + hq carries query row r of the item and query head hq of the kv
+// head's group of G = n_q / n_kv heads (G a power of two <= 16, r < 16 / G), so decode (1 row) and
+// chunked prefill (16 / G rows) share the kernel.
+// Per 16-token page:  S^T[token, n] = K[token, :] . Q[n, :]   (4 x mfma 16x16x32, K straight from
+// the page in operand order), online softmax per column, O^T[d, n] += V^T[d, token] P^T[token, n]
+// (8 x mfma 16x16x16; the score accumulator layout is exactly the P operand layout).
+// Waves split the pages; partial (max, sum, O) are merged in fixed order through LDS and, when the
+// context is split over several workgroups, through a scratch buffer and a second kernel.
+// =============================================================================================
+#define ATT_NEG (-1.0e30f)
+
+__device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
+                                                 const float* __restrict__ pl,
+                                                 const float* __restrict__ pacc, int nparts,
+                                                 size_t part_stride_ml, size_t part_stride_acc,
+                                                 int n, int d0, float* m_out, float* l_out,
+                                                 float* o8) {
+  float mt = ATT_NEG;
+  for (int w = 0; w < nparts; w++) mt = fmaxf(mt, pm[w * part_stride_ml + n]);
+  float L = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; e++) o8[e] = 0.f;
+  for (int w = 0; w < nparts; w++) {
+    float f = exp2f(pm[w * part_stride_ml + n] - mt);
+    L += f * pl[w * part_stride_ml + n];
+    const float* a = pacc + w * part_stride_acc + (size_t)n * 128 + d0;
+#pragma unroll
+    for (int e = 0; e < 8; e++) o8[e] += f * a[e];
+  }
+  *m_out = mt;
+  *l_out = L;
+}
+
+__global__ __launch_bounds__(256) void attention_mfma_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kpool, const bf16_t* __restrict__ vpool,
+    const AttnItem* __restrict__ items, const int32_t* __restrict__ page_table,
+    bf16_t* __restrict__ o, float* __restrict__ scratch, int nq, int nkv, int gshift,
+    int pt_stride, float scale2) {
+  __shared__ float s_acc[4 * 16 * 128];
+  __shared__ float s_m[4 * 16];
+  __shared__ float s_l[4 * 16];
+  const AttnItem it = items[blockIdx.x];
+  const int kvh = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane >> 4, n = lane & 15, r = n >> gshift, hq = n & ((1 << gshift) - 1);
+  const bool colvalid = r < it.nrows;
+  const int mypos = it.pos0 + r;
+  const int n_pages = (it.pos0 + it.nrows - 1) / RL_PAGE + 1;
+  const int nparts = nsplit * 4, part = split * 4 + wave;
+  const int per = (n_pages + nparts - 1) / nparts;
+  const int pg0 = part * per, pg1 = min(pg0 + per, n_pages);
+  const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
+
+  uint4 qreg[4];
+#pragma unroll
+  for (int c = 0; c < 4; c++) {
+    qreg[c] = make_uint4(0, 0, 0, 0);
+    if (colvalid)
+      qreg[c] = *(const uint4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
+  }
+  f32x4 acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m = ATT_NEG, l = 0.f;
+
+  uint4 kc[4], vc[4], kn[4], vn[4];
+  if (pg0 < pg1) {
+    size_t base = ((size_t)pt[pg0] * nkv + kvh) * 2048;
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      kn[c] = *(const uint4*)(kpool + base + c * 512 + lane * 8);
+      vn[c] = *(const uint4*)(vpool + base + c * 512 + lane * 8);
+    }
+  }
+  for (int pg = pg0; pg < pg1; pg++) {
+#pragma unroll
+    for (int c = 0; c < 4; c++) { kc[c] = kn[c]; vc[c] = vn[c]; }
+    if (pg + 1 < pg1) {
+      size_t base = ((size_t)pt[pg + 1] * nkv + kvh) * 2048;
+#pragma unroll
+      for (int c = 0; c < 4; c++) {
+        kn[c] = *(const uint4*)(kpool + base + c * 512 + lane * 8);
+        vn[c] = *(const uint4*)(vpool + base + c * 512 + lane * 8);
+      }
+    }
+    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[c]),
+                                                  __builtin_bit_cast(bf16x8, qreg[c]), S, 0, 0, 0);
+    float sv[4], mx = ATT_NEG;
+    bool vis[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      int tg = pg * RL_PAGE + 4 * g + i;
+      vis[i] = colvalid && tg <= mypos;
+      sv[i] = vis[i] ? S[i] * scale2 : ATT_NEG;
+      mx = fmaxf(mx, sv[i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float mn = fmaxf(m, mx);
+    float alpha = exp2f(m - mn);
+    float ps = 0.f;
+    s16x4 pb;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      float p = vis[i] ? exp2f(sv[i] - mn) : 0.f;
+      ps += p;
+      pb[i] = (short)f2bf(p);
+    }
+    l = l * alpha + ps;
+    m = mn;
+#pragma unroll
+    for (int jp = 0; jp < 4; jp++) {
+      s16x4 v0, v1;
+      v0[0] = (short)(vc[jp].x & 0xffff); v0[1] = (short)(vc[jp].x >> 16);
+      v0[2] = (short)(vc[jp].y & 0xffff); v0[3] = (short)(vc[jp].y >> 16);
+      v1[0] = (short)(vc[jp].z & 0xffff); v1[1] = (short)(vc[jp].z >> 16);
+      v1[2] = (short)(vc[jp].w & 0xffff); v1[3] = (short)(vc[jp].w >> 16);
+#pragma unroll
+      for (int i = 0; i < 4; i++) { acc[2 * jp][i] *= alpha; acc[2 * jp + 1][i] *= alpha; }
+      acc[2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pb, acc[2 * jp], 0, 0, 0);
+      acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0);
+    }
+  }
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  // wave partials -> LDS: acc[jb][i] is O^T[d = 16 jb + 4 g + i][column n]
+#pragma unroll
+  for (int jb = 0; jb < 8; jb++)
+#pragma unroll
+    for (int i = 0; i < 4; i++) s_acc[(wave * 16 + n) * 128 + jb * 16 + g * 4 + i] = acc[jb][i];
+  if (g == 0) { s_m[wave * 16 + n] = m; s_l[wave * 16 + n] = l; }
+  __syncthreads();
+  // 256 threads: column cn = tid / 16, dims d0 .. d0+7
+  const int cn = tid >> 4, d0 = (tid & 15) * 8;
+  float mt, L, o8[8];
+  attn_merge_store(s_m, s_l, s_acc, 4, 16, 16 * 128, cn, d0, &mt, &L, o8);
+  const int cr = cn >> gshift, chq = cn & ((1 << gshift) - 1);
+  if (nsplit == 1) {
+    if (cr < it.nrows) {
+      float inv = 1.0f / L;
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++)
+        w[e] = (uint32_t)f2bf(o8[2 * e] * inv) | ((uint32_t)f2bf(o8[2 * e + 1] * inv) << 16);
+      *(uint4*)(o + atile_off(it.row0 + cr, ((kvh << gshift) + chq) * 128 + d0, nq * 128)) =
+          make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  } else {
+    float* dst = scratch + (((size_t)blockIdx.x * nkv + kvh) * nsplit + split) * (16 * 130);
+#pragma unroll
+    for (int e = 0; e < 8; e++) dst[cn * 128 + d0 + e] = o8[e];
+    if ((tid & 15) == 0) { dst[16 * 128 + cn] = mt; dst[16 * 128 + 16 + cn] = L; }
+  }
+}
+
+// grid (n_items, nkv), block 256: merge the context splits of one (item, kv head)
+__global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ scratch,
+                                                              const AttnItem* __restrict__ items,
+                                                              bf16_t* __restrict__ o, int nq,
+                                                              int nkv, int gshift, int nsplit) {
+  const AttnItem it = items[blockIdx.x];
+  const int kvh = blockIdx.y, tid = threadIdx.x;
+  const float* src = scratch + (((size_t)blockIdx.x * nkv + kvh) * nsplit) * (16 * 130);
+  const int cn = tid >> 4, d0 = (tid & 15) * 8;
+  float mt, L, o8[8];
+  attn_merge_store(src + 16 * 128, src + 16 * 128 + 16, src, nsplit, 16 * 130, 16 * 130, cn, d0, &mt,
+                   &L, o8);
+  const int cr = cn >> gshift, chq = cn & ((1 << gshift) - 1);
+  if (cr < it.nrows) {
+    float inv = 1.0f / L;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++)
+      w[e] = (uint32_t)f2bf(o8[2 * e] * inv) | ((uint32_t)f2bf(o8[2 * e + 1] * inv) << 16);
+    *(uint4*)(o + atile_off(it.row0 + cr, ((kvh << gshift) + chq) * 128 + d0, nq * 128)) =
+        make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
+                           int n_items, const int32_t* page_table, bf16_t* o, float* scratch,
+                           const ModelDims& md, int splits) {
+  if (n_items <= 0) return;
+  if (splits < 1) splits = 1;
+  float scale2 = 1.4426950408889634f / sqrtf((float)md.d);
+  int gshift = 0;
+  while ((1 << gshift) < md.nq / md.nkv) gshift++;
+  dim3 grid(n_items, md.nkv, splits);
+  attention_mfma_kernel<<<grid, 256, 0, s>>>(q, (const bf16_t*)pool.k, (const bf16_t*)pool.v, items,
+                                             page_table, o, scratch, md.nq, md.nkv, gshift,
+                                             md.max_pages_per_traj, scale2);
+  if (splits > 1)
+    attention_merge_kernel<<<dim3(n_items, md.nkv), 256, 0, s>>>(scratch, items, o, md.nq, md.nkv,
+                                                                 gshift, splits);
+}

@@ -1,0 +1,86 @@
+// Shared device helpers and memory-layout functions for the rollout kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+#define RL_PAGE 16  // tokens per KV page
+
+__host__ __device__ __forceinline__ float bf2f(bf16_t x) {
+  union { uint32_t u; float f; } c;
+  c.u = (uint32_t)x << 16;
+  return c.f;
+}
+// round-to-nearest-even (finite inputs)
+__host__ __device__ __forceinline__ bf16_t f2bf(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void stf(float* p, float v) { *p = v; }
+__device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
+
+// ---------------------------------------------------------------------------------------
+// "A-tile" layout of a bf16 activation matrix X[rows, K] that feeds an MFMA GEMM as the
+// row operand.  Rows are grouped in tiles of 128, K in blocks of 16; inside one
+// (tile, k-block) the 4 KB are four 32x32x16 MFMA operands (32 rows each) stored in lane
+// order: lane = row % 32 + 32 * ((k % 16) / 8), 8 consecutive k per lane.  A GEMM workgroup
+// therefore copies its K-chunk of a tile into LDS as one contiguous block, and each
+// ds_read_b128 of an operand is conflict free.  Requires K % 16 == 0; the buffer holds
+// ceil(rows / 128) * 128 rows.
+// ---------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ size_t atile_off(int row, int k, int K) {
+  int mt = row >> 7, r = row & 127;
+  int mb = r >> 5, kb = k >> 4;
+  int lane = (r & 31) + (((k >> 3) & 1) << 5);
+  return ((((size_t)mt * (K >> 4) + kb) * 4 + mb) * 64 + lane) * 8 + (k & 7);
+}
+
+// ---------------------------------------------------------------------------------------
+// KV cache.  One page holds RL_PAGE tokens of one layer; pool layout [page][kv_head][block].
+// Plain block (fp32 mode, or head_dim != 128): [token][d].
+// MFMA block (bf16, head_dim 128, 4 KB for K and 4 KB for V):
+//   K: the 16 tokens x 128 dims are four 16x16x32 row operands (32 dims each) in lane
+//      order: lane = token + 16 * ((d % 32) / 8), 8 consecutive d per lane.
+//   V: stored transposed for the P.V product: eight 16x16x16 operands (16 dims each) whose
+//      lane = d % 16 + 16 * (token / 4) holds 4 consecutive tokens; two operands are
+//      interleaved per 16-byte lane slot so that one 16-byte load feeds two MFMAs.
+// ---------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ int kswz_off(int tok, int d) {
+  return ((((d >> 5) * 4 + ((d >> 3) & 3)) * 16 + tok) << 3) + (d & 7);
+}
+__host__ __device__ __forceinline__ int vswz_off(int tok, int d) {
+  int jb = d >> 4, lane = (d & 15) + ((tok >> 2) << 4);
+  return ((((jb >> 1) * 64 + lane) * 2 + (jb & 1)) << 2) + (tok & 3);
+}
+
+template <bool SWZ>
+__device__ __forceinline__ int kblk_off(int tok, int d, int D) {
+  return SWZ ? kswz_off(tok, d) : tok * D + d;
+}
+template <bool SWZ>
+__device__ __forceinline__ int vblk_off(int tok, int d, int D) {
+  return SWZ ? vswz_off(tok, d) : tok * D + d;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
