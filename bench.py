@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark: batched multi-turn rollout generation on one MI355X.
+
+One step = one full pass of the rollout hot path over one synthetic workload: prompt prefill
+(+ group fork), then per turn the decode steps and the observation append, then release.
+The default workload is the Qwen3-4B-shaped, 128-trajectory, 4-turn configuration ("cfg3").
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from synthetic import SHAPES, make_weight_blob, make_workload  # noqa: E402
+
+CONFIGS = {
+    # name: (shape, workload, description)
+    "cfg1": ("tiny", "cfg1"),
+    "cfg2": ("qwen3-0.6b", "cfg2"),
+    "cfg3": ("qwen3-4b", "cfg3"),
+    "cfg4": ("qwen3-4b", "cfg4"),
+}
+HBM_PEAK_GBS = 8000.0
+
+
+def run_rollout(engine, w, shape, stats):
+    """Replay the workload once (free-running sampling); returns generated token count."""
+    kvtok = shape.kv_bytes_per_token()
+    wbytes = shape.decode_weight_bytes()
+    ctx = {}
+    n_gen = 0
+    for ev in w.events:
+        kind = ev[0]
+        if kind == "append":
+            t0 = time.perf_counter()
+            engine.append_observation(ev[1], ev[2], ev[3])
+            stats["append_s"] += time.perf_counter() - t0
+            for i, c in zip(ev[1], ev[3]):
+                ctx[int(i)] = ctx.get(int(i), 0) + int(c)
+        elif kind == "fork":
+            t0 = time.perf_counter()
+            engine.fork(ev[1], ev[2])
+            stats["append_s"] += time.perf_counter() - t0
+            for d in ev[2]:
+                ctx[int(d)] = ctx[int(ev[1])]
+        elif kind == "decode":
+            t0 = time.perf_counter()
+            engine.decode_step(ev[1], ev[2], ev[3])
+            stats["decode_s"] += time.perf_counter() - t0
+            tot = 0
+            for i in ev[1]:
+                tot += ctx[int(i)]
+                ctx[int(i)] += 1
+            # algorithmic bytes of this decode step: weights once, every cached key/value once,
+            # one new key/value row per trajectory
+            stats["decode_bytes"] += wbytes + (tot + len(ev[1])) * kvtok
+            stats["decode_steps"] += 1
+            n_gen += len(ev[1])
+        elif kind == "release":
+            engine.release(ev[1])
+            for i in ev[1]:
+                ctx.pop(int(i), None)
+    return n_gen
+
+
+def cpu_baseline(blob, shape, budget_note):
+    """Time the CPU oracle (as is) on a small slice of the same workload."""
+    from oracle import OracleEngine
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    big = shape.linear_params() > 1e9
+    n_traj, prompt, steps = (2, 32, 2) if big else ((4, 64, 4) if shape.linear_params() > 1e8 else (4, 32, 16))
+    rng = np.random.default_rng(2)
+    toks = rng.integers(0, shape.vocab, n_traj * prompt, dtype=np.int32)
+    ids = np.arange(n_traj, dtype=np.int32)
+    t0 = time.perf_counter()
+    o = OracleEngine(blob, max_context=prompt + steps + 1, max_trajectories=n_traj,
+                     kv_pool_pages=n_traj * ((prompt + steps) // 16 + 2))
+    o.append_observation(ids, toks, np.full(n_traj, prompt, np.int32))
+    for _ in range(steps):
+        o.decode_step(ids, 1.0, 3)
+    dt = time.perf_counter() - t0
+    return {"value": n_traj * steps / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n_traj} trajectories x ({prompt}-token prompt prefill + {steps} sampled tokens) "
+                      f"at the same model shape, float64 numpy oracle, {dt:.1f} s wall; {budget_note}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="cfg3", choices=sorted(CONFIGS))
+    ap.add_argument("--scale", type=float, default=1.0,
+                    help="shrink every length of the workload (development only; not a valid headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timing-every", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (trajectories are independent; "
+              "see DESIGN.md for how the path would shard). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_2509_06980_amd as rl
+
+    shape_name, wl_name = CONFIGS[args.config]
+    shape = SHAPES[shape_name]
+    t0 = time.perf_counter()
+    blob = make_weight_blob(shape, seed=1)
+    t_blob = time.perf_counter() - t0
+    w = make_workload(wl_name, shape.vocab, scale=args.scale)
+    pages = w.n_trajectories * ((w.max_context + 15) // 16 + 2) + 64
+    t0 = time.perf_counter()
+    eng = rl.RolloutEngine(blob, max_context=w.max_context + 16, max_trajectories=w.n_trajectories,
+                           kv_pool_pages=pages)
+    t_load = time.perf_counter() - t0
+    print(f"[bench] {args.config}: {w.description}; blob {blob.nbytes / 1e9:.2f} GB in {t_blob:.1f}s, "
+          f"load {t_load:.1f}s, pool {pages} pages", file=sys.stderr, flush=True)
+
+    for i in range(args.warmup):
+        t0 = time.perf_counter()
+        run_rollout(eng, w, shape, dict(append_s=0.0, decode_s=0.0, decode_bytes=0.0, decode_steps=0))
+        print(f"[bench] warmup {i}: {time.perf_counter() - t0:.2f}s", file=sys.stderr, flush=True)
+
+    eng.timing_enable(args.timing_every)
+    eng.timing_read(reset=True)
+    stats = dict(append_s=0.0, decode_s=0.0, decode_bytes=0.0, decode_steps=0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_gen = 0
+    for i in range(args.steps):
+        n_gen += run_rollout(eng, w, shape, stats)
+        print(f"[bench] step {i}: {time.perf_counter() - t0:.2f}s elapsed", file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    attn_ms, attn_n, attn_bytes = eng.timing_read(reset=True)
+    eng.timing_enable(0)
+
+    roofline = None
+    if attn_n > 0:
+        achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "kernel": "attention_mfma_kernel" if eng.config["head_dim"] == 128 and
+                    eng.config["weight_dtype"] == 1 else "attention_generic_kernel",
+                    "avg_launch_us": round(attn_ms * 1e3 / attn_n, 2), "launches_timed": int(attn_n),
+                    "bytes_per_launch": round(attn_bytes / attn_n)}
+    out = {
+        "metric": "rollout_generated_tokens_per_s", "value": round(n_gen / dt, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt * 1e3 / max(args.steps, 1), 2), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.weight_dtype == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.config}: {shape_name} shape, {w.description}",
+                   "trajectories": w.n_trajectories, "generated_tokens_per_step": w.n_generated,
+                   "observation_tokens_per_step": w.n_observation, "prompt_tokens": w.n_prompt,
+                   "decode_steps_per_step": w.n_decode_steps, "max_context": w.max_context,
+                   "scale": args.scale},
+        "decode_only_tokens_per_s": round(n_gen / stats["decode_s"], 1) if stats["decode_s"] else None,
+        "decode_step_hbm": {"achieved": round(stats["decode_bytes"] / stats["decode_s"] / 1e9, 1),
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": round(stats["decode_bytes"] / stats["decode_s"] / 1e9 / HBM_PEAK_GBS, 4),
+                            "note": "algorithmic bytes of all decode steps / wall time inside rl_decode_step"}
+        if stats["decode_s"] else None,
+        "append_s_per_step": round(stats["append_s"] / max(args.steps, 1), 3),
+        "decode_s_per_step": round(stats["decode_s"] / max(args.steps, 1), 3),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(blob, shape, "baseline only, not the target")
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

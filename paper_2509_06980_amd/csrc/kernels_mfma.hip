@@ -45,12 +45,12 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 // each wave streams its own weight strip straight from HBM into registers, one chunk ahead.
 // blockIdx.z selects a K-slice (split-K, results combined with fp32 atomics).
 // =============================================================================================
-template <int EPI>
+template <int EPI, int D>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                         const bf16_t* __restrict__ Wp,
                                                         void* __restrict__ Cv, int M, int N, int K,
                                                         int chunks_per_split) {
-  __shared__ uint4 As[1024];
+  __shared__ u32x4 As[2][1024];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nb = blockIdx.x * 4 + wave;
   const bool active = nb * 32 < N;
@@ -58,47 +58,65 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
   const int nchunks = K >> 6;
   const int c0 = blockIdx.z * chunks_per_split;
   const int c1 = min(c0 + chunks_per_split, nchunks);
-  const uint4* Ag = (const uint4*)(A + (size_t)mt * K * 128);       // tile: 128 rows x K
-  const uint4* Wg = (const uint4*)(Wp + (size_t)nb * K * 32);       // strip: 32 columns x K
+  const u32x4* Ag = (const u32x4*)(A + (size_t)mt * K * 128);       // tile: 128 rows x K
+  const u32x4* Wg = (const u32x4*)(Wp + (size_t)(active ? nb : 0) * K * 32);  // strip: 32 columns x K
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; i++)
 #pragma unroll
     for (int j = 0; j < 16; j++) acc[i][j] = 0.f;
-  uint4 areg[4], bnext[4], bcur[4];
-  if (c0 < c1) {
-#pragma unroll
-    for (int i = 0; i < 4; i++) areg[i] = Ag[(size_t)c0 * 1024 + i * 256 + tid];
-    if (active) {
-#pragma unroll
-      for (int i = 0; i < 4; i++) bnext[i] = Wg[(size_t)(c0 * 4 + i) * 64 + lane];
-    }
+  // D chunks of A (for the whole workgroup) and of this wave's weight strip are kept in flight.
+  // Loads past the end of the K-slice are clamped to its last chunk (re-reads that hit in L2) so
+  // that the pipeline has no conditional register definitions.  Stages are spelled out (no
+  // arrays of stages) so that every buffer lives in registers.
+  const int clast = c1 - 1;
+  u32x4 a0[4], a1[4], a2[4], a3[4], b0[4], b1[4], b2[4], b3[4];
+#define GEMM_LOAD(AR, BR, CHUNK)                                            \
+  {                                                                         \
+    const int cl_ = min((CHUNK), clast);                                    \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                         \
+      AR[i] = Ag[(size_t)cl_ * 1024 + i * 256 + tid];                       \
+      BR[i] = Wg[(size_t)(cl_ * 4 + i) * 64 + lane];                        \
+    }                                                                       \
   }
-  for (int c = c0; c < c1; c++) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; i++) { As[i * 256 + tid] = areg[i]; bcur[i] = bnext[i]; }
-    __syncthreads();
-    if (c + 1 < c1) {
-#pragma unroll
-      for (int i = 0; i < 4; i++) areg[i] = Ag[(size_t)(c + 1) * 1024 + i * 256 + tid];
-      if (active) {
-#pragma unroll
-        for (int i = 0; i < 4; i++) bnext[i] = Wg[(size_t)((c + 1) * 4 + i) * 64 + lane];
-      }
-    }
-    if (active) {
-#pragma unroll
-      for (int kk = 0; kk < 4; kk++) {
-        bf16x8 b = __builtin_bit_cast(bf16x8, bcur[kk]);
-#pragma unroll
-        for (int mb = 0; mb < 4; mb++) {
-          bf16x8 a = __builtin_bit_cast(bf16x8, As[(kk * 4 + mb) * 64 + lane]);
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0);
-        }
-      }
-    }
+#define GEMM_STAGE(S, AR, BR)                                               \
+  if ((S) < D) {                                                            \
+    const int cc = c + (S);                                                 \
+    u32x4* buf = As[(S) & 1];                                               \
+    u32x4 bcur[4];                                                          \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                         \
+      buf[i * 256 + tid] = AR[i];                                           \
+      bcur[i] = BR[i];                                                      \
+    }                                                                       \
+    __syncthreads();                                                        \
+    GEMM_LOAD(AR, BR, cc + D)                                               \
+    {                                                                       \
+      /* past the end of the slice the weight operand is zeroed: the body stays branch free */ \
+      const unsigned keep = cc < c1 ? 0xffffffffu : 0u;                     \
+      _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                    \
+        u32x4 bm = bcur[kk] & keep;                                         \
+        bf16x8 b = __builtin_bit_cast(bf16x8, bm);                          \
+        _Pragma("unroll") for (int mb = 0; mb < 4; mb++) {                  \
+          bf16x8 a = __builtin_bit_cast(bf16x8, buf[(kk * 4 + mb) * 64 + lane]); \
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0); \
+        }                                                                   \
+      }                                                                     \
+    }                                                                       \
   }
+  GEMM_LOAD(a0, b0, c0)
+  if (D > 1) GEMM_LOAD(a1, b1, c0 + 1)
+  if (D > 2) GEMM_LOAD(a2, b2, c0 + 2)
+  if (D > 3) GEMM_LOAD(a3, b3, c0 + 3)
+  // the barrier inside a stage also orders its LDS store after every wave's reads of the same
+  // buffer two chunks earlier (D is even, so stage parity equals chunk parity)
+  for (int c = c0; c < c1; c += D) {
+    GEMM_STAGE(0, a0, b0)
+    GEMM_STAGE(1, a1, b1)
+    GEMM_STAGE(2, a2, b2)
+    GEMM_STAGE(3, a3, b3)
+  }
+#undef GEMM_LOAD
+#undef GEMM_STAGE
   if (!active) return;
   const int col = nb * 32 + (lane & 31);
 #pragma unroll
@@ -123,6 +141,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
   }
 }
 
+int g_gemm_depth = 4;   // chunks in flight per workgroup (tuning knob)
+
+template <int D>
+static void gemm_launch_d(hipStream_t s, dim3 grid, const bf16_t* A, const bf16_t* Wp, void* C, int M,
+                          int N, int K, int epilogue, int cps) {
+  if (epilogue == EPI_STORE)
+    gemm_mfma_kernel<EPI_STORE, D><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+  else if (epilogue == EPI_ATOMIC_ADD)
+    gemm_mfma_kernel<EPI_ATOMIC_ADD, D><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+  else
+    gemm_mfma_kernel<EPI_SWIGLU, D><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+}
+
 void launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
                       int K, int epilogue, int splits) {
   if (M <= 0) return;
@@ -132,12 +163,10 @@ void launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C,
   int cps = (nchunks + splits - 1) / splits;
   splits = (nchunks + cps - 1) / cps;
   dim3 grid((N + 127) / 128, (M + 127) / 128, splits);
-  if (epilogue == EPI_STORE)
-    gemm_mfma_kernel<EPI_STORE><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
-  else if (epilogue == EPI_ATOMIC_ADD)
-    gemm_mfma_kernel<EPI_ATOMIC_ADD><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
-  else
-    gemm_mfma_kernel<EPI_SWIGLU><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+  switch (g_gemm_depth) {
+    case 2: gemm_launch_d<2>(s, grid, A, Wp, C, M, N, K, epilogue, cps); break;
+    default: gemm_launch_d<4>(s, grid, A, Wp, C, M, N, K, epilogue, cps); break;
+  }
 }
 
 // =============================================================================================

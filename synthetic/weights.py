@@ -18,9 +18,11 @@ library):
                g_final[H]
                lm_head[V,H]            (absent when tie_embeddings = 1)
 
-Every tensor is drawn from its own generator keyed by (seed, tensor index), so the
-bytes do not depend on how many threads fill the blob.
+Every 4M-element piece of a tensor is drawn from its own generator keyed by
+(seed, tensor index, piece index), so the bytes do not depend on how many threads
+fill the blob.
 """
+import os
 import struct
 from concurrent.futures import ThreadPoolExecutor
 
@@ -66,13 +68,15 @@ def _to_bf16_bits(x32: np.ndarray) -> np.ndarray:
 
 def make_weight_blob(shape: ModelShape, seed: int = 1, weight_std: float = 0.02,
                      gain_std: float = 0.0, zero_linear: bool = False,
-                     threads: int = 8) -> np.ndarray:
+                     threads: int = 0) -> np.ndarray:
     """Return the blob as a uint8 array.
 
     Linear / embedding / lm-head entries ~ N(0, weight_std^2); RMSNorm gains are
     1 + gain_std * N(0,1) (exactly 1.0 when gain_std = 0).  `zero_linear` makes
     every non-gain tensor zero (closed-form test case).
     """
+    if threads <= 0:
+        threads = min(16, os.cpu_count() or 1)
     table = tensor_table(shape)
     el = 2 if shape.weight_dtype == 1 else 4
     sizes = [int(np.prod(dims)) for _, dims, _ in table]
@@ -85,10 +89,14 @@ def make_weight_blob(shape: ModelShape, seed: int = 1, weight_std: float = 0.02,
     blob[:len(hdr)] = np.frombuffer(hdr, dtype=np.uint8)
     offs = np.concatenate([[0], np.cumsum(sizes)]) * el + BLOB_HEADER_BYTES
 
-    def fill(i):
+    CH = 1 << 22          # elements per task; each task has its own generator
+
+    def fill(task):
+        i, c = task
         _, dims, is_gain = table[i]
-        n = sizes[i]
-        rng = np.random.default_rng(np.random.SeedSequence([seed, i]))
+        a, b = c * CH, min(sizes[i], (c + 1) * CH)
+        n = b - a
+        rng = np.random.default_rng(np.random.SeedSequence([seed, i, c]))
         if is_gain:
             x = np.ones(n, dtype=np.float32)
             if gain_std:
@@ -98,16 +106,17 @@ def make_weight_blob(shape: ModelShape, seed: int = 1, weight_std: float = 0.02,
         else:
             x = rng.standard_normal(n, dtype=np.float32)
             x *= np.float32(weight_std)
-        dst = blob[offs[i]:offs[i + 1]]
+        dst = blob[offs[i] + a * el:offs[i] + b * el]
         if el == 2:
             dst.view(np.uint16)[:] = _to_bf16_bits(x)
         else:
             dst.view(np.float32)[:] = x
 
+    tasks = [(i, c) for i in range(len(table)) for c in range((sizes[i] + CH - 1) // CH)]
     if threads > 1 and sum(sizes) > (1 << 24):
         with ThreadPoolExecutor(threads) as ex:
-            list(ex.map(fill, range(len(table))))
+            list(ex.map(fill, tasks))
     else:
-        for i in range(len(table)):
-            fill(i)
+        for t in tasks:
+            fill(t)
     return blob
