@@ -146,18 +146,21 @@ def main():
         print(f"[bench] step {i}: {time.perf_counter() - t0:.2f}s elapsed", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    attn_ms, attn_n, attn_bytes = eng.timing_read(reset=True)
+    attn_ms, attn_n, attn_bytes, attn_unique = eng.timing_read(reset=True)
     eng.timing_enable(0)
 
     roofline = None
     if attn_n > 0:
-        achieved = attn_bytes / (attn_ms * 1e-3) / 1e9
+        # algorithmic bytes = keys + values of the DISTINCT pages the step references (prompt pages
+        # shared by a forked group are needed once); the per-trajectory count is kept beside it
+        achieved = attn_unique / (attn_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "achieved_counting_shared_pages_per_trajectory": round(attn_bytes / (attn_ms * 1e-3) / 1e9, 1),
                     "kernel": "attention_mfma_kernel" if eng.config["head_dim"] == 128 and
                     eng.config["weight_dtype"] == 1 else "attention_generic_kernel",
                     "avg_launch_us": round(attn_ms * 1e3 / attn_n, 2), "launches_timed": int(attn_n),
-                    "bytes_per_launch": round(attn_bytes / attn_n)}
+                    "bytes_per_launch": round(attn_unique / attn_n)}
     out = {
         "metric": "rollout_generated_tokens_per_s", "value": round(n_gen / dt, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -151,11 +151,12 @@ uint32_t rl_uniform_u32(uint64_t seed, int32_t traj_id, int32_t position);
  * Kernel timing for benchmarks: when enabled, every `every`-th decode step brackets its
  * decode-attention launches with HIP events on the engine's stream.  rl_timing_read returns
  * the accumulated duration, the number of timed launches and the bytes of keys / values
- * those launches had to read (sum over rows of context length x bytes per token per layer).
+ * those launches had to read: attn_kv_bytes sums context length x bytes per token per layer over
+ * the rows; attn_kv_unique_bytes counts a page shared by several trajectories of the step once.
  */
 int rl_timing_enable(rl_model* m, int32_t every);
 int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches, double* attn_kv_bytes,
-                   int reset);
+                   double* attn_kv_unique_bytes, int reset);
 
 #ifdef __cplusplus
 }

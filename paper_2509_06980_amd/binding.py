@@ -70,7 +70,7 @@ def load_library():
     lib.rl_uniform_u32.restype = C.c_uint32
     lib.rl_timing_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.rl_timing_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
-                                   C.POINTER(C.c_double), C.c_int]
+                                   C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int]
     _lib = lib
     return lib
 
@@ -201,6 +201,7 @@ class RolloutEngine:
         _check(self._lib.rl_timing_enable(self._h, int(every)))
 
     def timing_read(self, reset=True):
-        ms, n, b = C.c_double(), C.c_int64(), C.c_double()
-        _check(self._lib.rl_timing_read(self._h, C.byref(ms), C.byref(n), C.byref(b), int(reset)))
-        return ms.value, n.value, b.value
+        ms, n, b, u = C.c_double(), C.c_int64(), C.c_double(), C.c_double()
+        _check(self._lib.rl_timing_read(self._h, C.byref(ms), C.byref(n), C.byref(b), C.byref(u),
+                                        int(reset)))
+        return ms.value, n.value, b.value, u.value

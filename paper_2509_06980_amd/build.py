@@ -11,7 +11,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]
 SOURCES = {
     "kernels_generic.hip": [],
-    "kernels_mfma.hip": ["-munsafe-fp-atomics"],
+    "kernels_mfma.hip": [],
     # the sampler's integer weights must not see fused multiply-adds
     "kernels_sampler.hip": ["-ffp-contract=off"],
     "engine.hip": [],

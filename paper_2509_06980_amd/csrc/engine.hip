@@ -68,7 +68,8 @@ struct rl_model {
   int32_t* page_table = nullptr;
   // work buffers
   int Mcap = 0, Rl = 0, rows_per_item = 1;
-  float *h = nullptr, *qkv = nullptr, *gu = nullptr, *logits = nullptr, *attn_scratch = nullptr;
+  float *h = nullptr, *qkv = nullptr, *ph = nullptr, *gu = nullptr, *logits = nullptr, *attn_scratch = nullptr;
+  int pending_parts = 0;   // split-K partial sums of the last down-projection still to be added to h
   void *xa = nullptr, *xo = nullptr, *xm = nullptr, *qb = nullptr;
   int32_t *d_meta = nullptr, *h_meta = nullptr;  // device / pinned staging for per-call integers
   size_t meta_ints = 0;
@@ -86,7 +87,9 @@ struct rl_model {
   // timing
   int timing_every = 0;
   int64_t decode_steps = 0, attn_launches = 0;
-  double attn_ms = 0.0, attn_bytes = 0.0;
+  double attn_ms = 0.0, attn_bytes = 0.0, attn_unique_bytes = 0.0;
+  std::vector<uint32_t> page_stamp;   // per page: last timed step that counted it
+  uint32_t stamp = 0;
   std::vector<hipEvent_t> ev;
 
   int dalloc(void** p, size_t bytes, bool zero = false) {
@@ -160,8 +163,8 @@ void forward_generic(rl_model* m, int M, const RowMeta& r) {
     const LayerW& w = m->layers[l];
     launch_rmsnorm<TW, TA>(s, m->h, (const TW*)w.g_in, (TA*)m->xa, M, H, md.eps, false);
     launch_gemm_generic<TA, TW>(s, (const TA*)m->xa, (const TW*)w.wqkv, m->qkv, M, qw + 2 * kvw, H, false);
-    launch_qkrope<TW, TA, TA, false>(s, m->qkv, (const TW*)w.gq, (const TW*)w.gk, m->rope_cs, r.pos,
-                                     r.slot, m->page_table, (TA*)m->qb, m->pools[l], md, M, false);
+    launch_qkrope<TW, TA, TA, false>(s, m->qkv, 1, 0, (const TW*)w.gq, (const TW*)w.gk, m->rope_cs,
+                                     r.pos, r.slot, m->page_table, (TA*)m->qb, m->pools[l], md, M);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
     launch_attention_generic<TA, TA, false>(s, (const TA*)m->qb, m->pools[l], r.pos, r.slot,
                                             m->page_table, (TA*)m->xo, md, M, false);
@@ -174,41 +177,54 @@ void forward_generic(rl_model* m, int M, const RowMeta& r) {
   }
 }
 
-// Split-K factor for the skinny (decode) GEMMs.  Measured on MI355X at M = 128: about 150
-// workgroups already saturate what the kernel can pull, and every extra split adds M x N fp32
-// atomics, so aim for ~150 workgroups and keep at least four 64-k chunks per split.
-int gemm_splits(int M, int N, int K) {
+// Split-K factor of a weight-streaming GEMM (tile 128 x 128, 4 waves).  Measured on MI355X: one CU
+// sustains only ~20 GB/s of HBM reads, so a decode GEMM wants a workgroup on every CU: aim for
+// ~240 workgroups, at least four 64-k chunks per split, at most kMaxSplits partial sums (each
+// costs M x N floats of traffic).  Prefill-sized GEMMs already have many row tiles.
+struct GemmPlan { int nw, splits; };
+const int kMaxSplits = 12;
+GemmPlan plan_gemm(int M, int N, int K, bool can_split) {
   int tiles = ((N + 127) / 128) * ((M + 127) / 128);
-  int want = (150 + tiles - 1) / tiles;
-  int max_s = std::max(1, K / 256);
-  return std::max(1, std::min(want, max_s));
+  int s = 1;
+  if (can_split && M <= 256 && tiles < 240) {
+    s = (240 + tiles / 2) / tiles;
+    s = std::min({s, kMaxSplits, std::max(1, K / 256)});
+  }
+  return GemmPlan{4, std::max(1, s)};
 }
 
+// Leaves the last down-projection as m->pending_parts partial sums in m->ph (added by the next
+// add_rmsnorm: the next layer's, or the final norm before the lm-head).
 void forward_mfma(rl_model* m, int M, const RowMeta& r) {
   hipStream_t s = m->stream;
   const ModelDims& md = m->md;
-  int H = md.H, qw = md.nq * md.d, kvw = md.nkv * md.d, I = md.I;
+  int H = md.H, qw = md.nq * md.d, kvw = md.nkv * md.d, I = md.I, QW = qw + 2 * kvw;
   launch_embed<bf16_t>(s, (const bf16_t*)m->embed, r.tok, m->h, M, H);
+  int pend = 0;
   for (int l = 0; l < md.L; l++) {
     const LayerW& w = m->layers[l];
-    launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)w.g_in, (bf16_t*)m->xa, M, H, md.eps, true);
-    int sq = gemm_splits(M, qw + 2 * kvw, H);
-    launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wqkv, m->qkv, M, qw + 2 * kvw, H,
-                     sq > 1 ? EPI_ATOMIC_ADD : EPI_STORE, sq);
-    launch_qkrope<bf16_t, bf16_t, bf16_t, true>(s, m->qkv, (const bf16_t*)w.gq, (const bf16_t*)w.gk,
-                                                m->rope_cs, r.pos, r.slot, m->page_table,
-                                                (bf16_t*)m->qb, m->pools[l], md, M, true);
+    launch_add_rmsnorm(s, m->h, m->ph, pend, (size_t)M * H, (const bf16_t*)w.g_in, (bf16_t*)m->xa, M, H, md.eps);
+    GemmPlan pq = plan_gemm(M, QW, H, true);
+    int sq = launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wqkv, m->qkv, M, QW, H, EPI_STORE,
+                              pq.splits, pq.nw);
+    launch_qkrope<bf16_t, bf16_t, bf16_t, true>(s, m->qkv, sq, (size_t)M * QW, (const bf16_t*)w.gq,
+                                                (const bf16_t*)w.gk, m->rope_cs, r.pos, r.slot,
+                                                m->page_table, (bf16_t*)m->qb, m->pools[l], md, M);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
     launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, m->page_table,
                           (bf16_t*)m->xo, m->attn_scratch, md, r.attn_splits);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
-    launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->h, M, H, qw, EPI_ATOMIC_ADD,
-                     gemm_splits(M, H, qw));
-    launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)w.g_post, (bf16_t*)m->xa, M, H, md.eps, true);
-    launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wgu, m->xm, M, 2 * I, H, EPI_SWIGLU, 1);
-    launch_gemm_mfma(s, (const bf16_t*)m->xm, (const bf16_t*)w.wdown, m->h, M, H, I, EPI_ATOMIC_ADD,
-                     gemm_splits(M, H, I));
+    GemmPlan po = plan_gemm(M, H, qw, true);
+    int so = launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->ph, M, H, qw, EPI_STORE,
+                              po.splits, po.nw);
+    launch_add_rmsnorm(s, m->h, m->ph, so, (size_t)M * H, (const bf16_t*)w.g_post, (bf16_t*)m->xa, M, H, md.eps);
+    GemmPlan pg = plan_gemm(M, 2 * I, H, false);
+    launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wgu, m->xm, M, 2 * I, H, EPI_SWIGLU, 1, pg.nw);
+    GemmPlan pd = plan_gemm(M, H, I, true);
+    pend = launch_gemm_mfma(s, (const bf16_t*)m->xm, (const bf16_t*)w.wdown, m->ph, M, H, I, EPI_STORE,
+                            pd.splits, pd.nw);
   }
+  m->pending_parts = pend;
 }
 
 void forward_rows(rl_model* m, int M, const RowMeta& r) {
@@ -222,11 +238,15 @@ void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done) {
   hipStream_t s = m->stream;
   const ModelDims& md = m->md;
   if (m->mfma) {
-    if (!norm_done)
-      launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, M, md.H, md.eps, true);
+    if (!norm_done) {
+      launch_add_rmsnorm(s, m->h, m->ph, m->pending_parts, (size_t)M * md.H, (const bf16_t*)m->g_final,
+                         (bf16_t*)m->xa, M, md.H, md.eps);
+      m->pending_parts = 0;
+    }
     // r0 is a multiple of 128: skip whole A tiles
+    GemmPlan pl = plan_gemm(R, md.V, md.H, false);
     launch_gemm_mfma(s, (const bf16_t*)m->xa + (size_t)r0 * md.H, (const bf16_t*)m->lm_head, m->logits,
-                     R, md.V, md.H, EPI_STORE, 1);
+                     R, md.V, md.H, EPI_STORE, 1, pl.nw);
   } else if (m->bf16) {
     if (!norm_done)
       launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, M, md.H, md.eps, false);
@@ -425,6 +445,21 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
   if (rc) return rc;
   bool timed = m->timing_every > 0 && (m->decode_steps % m->timing_every) == 0;
   m->decode_steps++;
+  double kvu = 0.0;
+  if (timed) {   // bytes of distinct pages: pages shared by forked trajectories count once
+    if (m->page_stamp.size() != m->refcount.size()) m->page_stamp.assign(m->refcount.size(), 0);
+    m->stamp++;
+    double tokb = 2.0 * m->md.nkv * m->md.d * m->el;
+    for (Traj* t : ts) {
+      int nt = (int)t->tokens.size();
+      for (int pg = 0; pg * RL_PAGE < nt; pg++) {
+        int page = t->pages[pg];
+        if (m->page_stamp[page] == m->stamp) continue;
+        m->page_stamp[page] = m->stamp;
+        kvu += tokb * std::min(RL_PAGE, nt - pg * RL_PAGE);
+      }
+    }
+  }
   RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, n, pick_attn_splits(m, n, max_pos), kvb, timed};
   forward_rows(m, n, r);
   lm_head_rows(m, n, 0, n, false);
@@ -443,6 +478,7 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
         m->attn_ms += ms;
         m->attn_launches++;
         m->attn_bytes += kvb;
+        m->attn_unique_bytes += kvu;
       }
     }
   }
@@ -583,7 +619,10 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   size_t Mc = m->Mcap;
   size_t ael = m->bf16 ? 2 : 4;
   TRY(m->dalloc((void**)&m->h, Mc * H * 4, true));
-  TRY(m->dalloc((void**)&m->qkv, Mc * (qw + 2 * kvw) * 4, true));
+  // split-K partial sums: up to kMaxSplits slices of a decode-sized batch, or one prefill pass
+  size_t prow = m->mfma ? std::max<size_t>(Mc, (size_t)kMaxSplits * std::min(256, round_up(rt->max_trajectories, 128))) : Mc;
+  TRY(m->dalloc((void**)&m->qkv, prow * (qw + 2 * kvw) * 4, true));
+  if (m->mfma) TRY(m->dalloc((void**)&m->ph, prow * H * 4, true));
   TRY(m->dalloc(&m->xa, Mc * H * ael, true));
   TRY(m->dalloc(&m->xo, Mc * qw * ael, true));
   TRY(m->dalloc(&m->xm, Mc * I * ael, true));
@@ -919,11 +958,12 @@ extern "C" int rl_timing_enable(rl_model* m, int32_t every) {
 }
 
 extern "C" int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches,
-                              double* attn_kv_bytes, int reset) {
+                              double* attn_kv_bytes, double* attn_kv_unique_bytes, int reset) {
   if (!m) return fail(RL_E_ARG, "null model");
   if (attn_ms) *attn_ms = m->attn_ms;
   if (attn_launches) *attn_launches = m->attn_launches;
   if (attn_kv_bytes) *attn_kv_bytes = m->attn_bytes;
-  if (reset) { m->attn_ms = 0.0; m->attn_launches = 0; m->attn_bytes = 0.0; }
+  if (attn_kv_unique_bytes) *attn_kv_unique_bytes = m->attn_unique_bytes;
+  if (reset) { m->attn_ms = 0.0; m->attn_launches = 0; m->attn_bytes = 0.0; m->attn_unique_bytes = 0.0; }
   return RL_OK;
 }

@@ -41,11 +41,18 @@ void launch_gemm_generic(hipStream_t s, const TA* A, const TW* W, float* C, int 
                          bool accumulate);
 
 // q/k per-head RMSNorm (optional), rotate-half RoPE, q -> qout [M, nq*d] row-major, k and v into
-// the paged cache at (page_table[slot][pos/16], pos%16).  zero_qkv: clear qkv afterwards.
+// the paged cache at (page_table[slot][pos/16], pos%16).  The projection arrives as n_part
+// split-K partial sums (qkv + p * part_stride), added here in ascending order.
 template <typename TW, typename TA, typename TKV, bool SWZ>
-void launch_qkrope(hipStream_t s, float* qkv, const TW* gq, const TW* gk, const float* rope_cs,
-                   const int32_t* row_pos, const int32_t* row_slot, const int32_t* page_table,
-                   TA* qout, KvPool pool, const ModelDims& md, int M, bool zero_qkv);
+void launch_qkrope(hipStream_t s, const float* qkv, int n_part, size_t part_stride, const TW* gq,
+                   const TW* gk, const float* rope_cs, const int32_t* row_pos,
+                   const int32_t* row_slot, const int32_t* page_table, TA* qout, KvPool pool,
+                   const ModelDims& md, int M);
+
+// h += sum of n_part split-K partial sums (ascending order), then out = rmsnorm(h) * g in A-tile
+// layout (bf16 MFMA path).
+void launch_add_rmsnorm(hipStream_t s, float* h, const float* parts, int n_part, size_t part_stride,
+                        const bf16_t* g, bf16_t* out, int M, int H, float eps);
 
 template <typename TA, typename TKV, bool SWZ>
 void launch_attention_generic(hipStream_t s, const TA* q, KvPool pool, const int32_t* row_pos,
@@ -57,12 +64,14 @@ template <typename TA>
 void launch_swiglu(hipStream_t s, const float* gu, TA* m, int M, int I, bool atile);
 
 // ---- MFMA kernels (bf16, head_dim 128) -------------------------------------------------------
-enum GemmEpilogue { EPI_STORE = 0, EPI_ATOMIC_ADD = 1, EPI_SWIGLU = 2 };
-// A: bf16 A-tile layout [ceil(M/128)*128, K]; Wp: weights in 32-column operand strips
-// (see repack kernels); C: fp32 row-major [M, N] (EPI_STORE / EPI_ATOMIC_ADD) or bf16 A-tile
-// [.., N/2] (EPI_SWIGLU, gate/up interleaved in 16-column groups).  K % 64 == 0, N % 32 == 0.
-void launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
-                      int K, int epilogue, int splits);
+enum GemmEpilogue { EPI_STORE = 0, EPI_SWIGLU = 2 };
+// A: bf16 A-tile layout [ceil(M/128)*128, K]; Wp: repacked weights (see repack kernel).
+// EPI_STORE: split-K slice z writes its fp32 partial sum to C + z * M * N (row-major [M, N]); the
+// consumer adds the `splits` partials.  EPI_SWIGLU (splits = 1): C is bf16 A-tile [.., N/2], gate
+// and up interleaved in 16-column groups.  nw = waves per workgroup (2 or 4): tile 128 x 32*nw.
+// K % 64 == 0, N % 32 == 0.  Returns the number of splits actually used.
+int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
+                     int K, int epilogue, int splits, int nw);
 // W[N,K] row-major -> operand strips.  interleave16: rows come from two matrices Wg, Wu
 // ([N/2,K] each) interleaved in groups of 16 (gate, up, gate, up, ...).
 void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16_t* Wp, int N,

@@ -26,11 +26,60 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const TW* __restrict
   __syncthreads();
   float tot = red[0] + red[1] + red[2] + red[3];
   float inv = 1.0f / sqrtf(tot / (float)H + eps);
-  for (int j = threadIdx.x; j < H; j += 256) {
-    float y = x[j] * inv * ldf(g + j);
-    if (ATILE) stf(out + atile_off(row, j, H), y);
-    else stf(out + (size_t)row * H + j, y);
+  if (ATILE) {
+    // 8 consecutive k share one 16-byte lane slot of the A-tile layout (H % 16 == 0)
+    for (int j = threadIdx.x * 8; j < H; j += 256 * 8) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        float y0 = x[j + 2 * e] * inv * ldf(g + j + 2 * e);
+        float y1 = x[j + 2 * e + 1] * inv * ldf(g + j + 2 * e + 1);
+        w[e] = (uint32_t)f2bf(y0) | ((uint32_t)f2bf(y1) << 16);
+      }
+      *(uint4*)((bf16_t*)out + atile_off(row, j, H)) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  } else {
+    for (int j = threadIdx.x; j < H; j += 256) stf(out + (size_t)row * H + j, x[j] * inv * ldf(g + j));
   }
+}
+
+// grid M, block 256: h[row] += sum_p parts[p][row]; out = rmsnorm(h[row]) * g, A-tile layout
+__global__ void add_rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ parts, int n_part,
+                                   size_t part_stride, const bf16_t* __restrict__ g,
+                                   bf16_t* __restrict__ out, int H, float eps) {
+  __shared__ float red[4];
+  int row = blockIdx.x;
+  float* x = h + (size_t)row * H;
+  const float* pr = parts + (size_t)row * H;
+  float ss = 0.f;
+  for (int j = threadIdx.x * 4; j < H; j += 1024) {
+    float4 v = *(const float4*)(x + j);
+    for (int p = 0; p < n_part; p++) {
+      float4 u = *(const float4*)(pr + p * part_stride + j);
+      v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    if (n_part > 0) *(float4*)(x + j) = v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();   // also makes every thread's updated h visible to the block
+  float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
+  for (int j = threadIdx.x * 8; j < H; j += 2048) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      float y0 = x[j + 2 * e] * inv * bf2f(g[j + 2 * e]);
+      float y1 = x[j + 2 * e + 1] * inv * bf2f(g[j + 2 * e + 1]);
+      w[e] = (uint32_t)f2bf(y0) | ((uint32_t)f2bf(y1) << 16);
+    }
+    *(uint4*)(out + atile_off(row, j, H)) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+void launch_add_rmsnorm(hipStream_t s, float* h, const float* parts, int n_part, size_t part_stride,
+                        const bf16_t* g, bf16_t* out, int M, int H, float eps) {
+  if (M > 0) add_rmsnorm_kernel<<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps);
 }
 
 template <typename TA, typename TW>
@@ -78,25 +127,27 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const TA* __restrict_
 
 // grid (M, nq + 2 nkv), block 64
 template <typename TW, typename TA, typename TKV, bool SWZ>
-__global__ void qkrope_kernel(float* __restrict__ qkv, const TW* __restrict__ gq,
+__global__ void qkrope_kernel(const float* __restrict__ qkv, int n_part, size_t part_stride,
+                              const TW* __restrict__ gq,
                               const TW* __restrict__ gk, const float* __restrict__ rope_cs,
                               const int32_t* __restrict__ row_pos,
                               const int32_t* __restrict__ row_slot,
                               const int32_t* __restrict__ page_table, TA* __restrict__ qout,
                               TKV* __restrict__ kpool, TKV* __restrict__ vpool, int nq, int nkv,
-                              int d, float eps, int qk_norm, int pt_stride, int zero_qkv) {
+                              int d, float eps, int qk_norm, int pt_stride) {
   int row = blockIdx.x, hd = blockIdx.y, half = d >> 1;
   int pos = row_pos[row];
-  float* x = qkv + (size_t)row * (nq + 2 * nkv) * d + (size_t)hd * d;
+  const float* x = qkv + (size_t)row * (nq + 2 * nkv) * d + (size_t)hd * d;
   bool is_q = hd < nq, is_v = hd >= nq + nkv;
   float x1[2], x2[2];
   float ss = 0.f;
   int cnt = 0;
   for (int i = threadIdx.x; i < half; i += 64, cnt++) {
-    x1[cnt] = x[i];
-    x2[cnt] = x[i + half];
-    ss += x1[cnt] * x1[cnt] + x2[cnt] * x2[cnt];
-    if (zero_qkv) { x[i] = 0.f; x[i + half] = 0.f; }
+    float u = x[i], w = x[i + half];
+    for (int p = 1; p < n_part; p++) { u += x[p * part_stride + i]; w += x[p * part_stride + i + half]; }
+    x1[cnt] = u;
+    x2[cnt] = w;
+    ss += u * u + w * w;
   }
   ss = wave_sum(ss);
   float inv = (qk_norm && !is_v) ? 1.0f / sqrtf(ss / (float)d + eps) : 1.0f;
@@ -240,18 +291,19 @@ template void launch_gemm_generic<float, float>(hipStream_t, const float*, const
 template void launch_gemm_generic<bf16_t, bf16_t>(hipStream_t, const bf16_t*, const bf16_t*, float*, int, int, int, bool);
 
 template <typename TW, typename TA, typename TKV, bool SWZ>
-void launch_qkrope(hipStream_t s, float* qkv, const TW* gq, const TW* gk, const float* rope_cs,
-                   const int32_t* row_pos, const int32_t* row_slot, const int32_t* page_table,
-                   TA* qout, KvPool pool, const ModelDims& md, int M, bool zero_qkv) {
+void launch_qkrope(hipStream_t s, const float* qkv, int n_part, size_t part_stride, const TW* gq,
+                   const TW* gk, const float* rope_cs, const int32_t* row_pos,
+                   const int32_t* row_slot, const int32_t* page_table, TA* qout, KvPool pool,
+                   const ModelDims& md, int M) {
   if (M <= 0) return;
   dim3 grid(M, md.nq + 2 * md.nkv);
   qkrope_kernel<TW, TA, TKV, SWZ><<<grid, 64, 0, s>>>(
-      qkv, gq, gk, rope_cs, row_pos, row_slot, page_table, qout, (TKV*)pool.k, (TKV*)pool.v, md.nq,
-      md.nkv, md.d, md.eps, md.qk_norm, md.max_pages_per_traj, zero_qkv ? 1 : 0);
+      qkv, n_part, part_stride, gq, gk, rope_cs, row_pos, row_slot, page_table, qout, (TKV*)pool.k,
+      (TKV*)pool.v, md.nq, md.nkv, md.d, md.eps, md.qk_norm, md.max_pages_per_traj);
 }
-template void launch_qkrope<float, float, float, false>(hipStream_t, float*, const float*, const float*, const float*, const int32_t*, const int32_t*, const int32_t*, float*, KvPool, const ModelDims&, int, bool);
-template void launch_qkrope<bf16_t, bf16_t, bf16_t, false>(hipStream_t, float*, const bf16_t*, const bf16_t*, const float*, const int32_t*, const int32_t*, const int32_t*, bf16_t*, KvPool, const ModelDims&, int, bool);
-template void launch_qkrope<bf16_t, bf16_t, bf16_t, true>(hipStream_t, float*, const bf16_t*, const bf16_t*, const float*, const int32_t*, const int32_t*, const int32_t*, bf16_t*, KvPool, const ModelDims&, int, bool);
+template void launch_qkrope<float, float, float, false>(hipStream_t, const float*, int, size_t, const float*, const float*, const float*, const int32_t*, const int32_t*, const int32_t*, float*, KvPool, const ModelDims&, int);
+template void launch_qkrope<bf16_t, bf16_t, bf16_t, false>(hipStream_t, const float*, int, size_t, const bf16_t*, const bf16_t*, const float*, const int32_t*, const int32_t*, const int32_t*, bf16_t*, KvPool, const ModelDims&, int);
+template void launch_qkrope<bf16_t, bf16_t, bf16_t, true>(hipStream_t, const float*, int, size_t, const bf16_t*, const bf16_t*, const float*, const int32_t*, const int32_t*, const int32_t*, bf16_t*, KvPool, const ModelDims&, int);
 
 template <typename TA, typename TKV, bool SWZ>
 void launch_attention_generic(hipStream_t s, const TA* q, KvPool pool, const int32_t* row_pos,

@@ -4,22 +4,26 @@
 #include "kernels.h"
 
 // =============================================================================================
-// Weight repack: W[N,K] row-major -> strips of 32 output columns; inside a strip, one 1 KB block
-// per 16 k holds a 32x32x16 MFMA column operand in lane order
-// (lane = n % 32 + 32 * ((k % 16) / 8), 8 consecutive k per lane).  A wave streaming its strip
-// reads one contiguous run of K * 64 bytes.
+// Weight repack: W[N,K] row-major -> [K/64 chunks][N/32 strips][4 k-blocks][64 lanes][8].  One
+// (chunk, strip) cell is 4 KB: four 32x32x16 MFMA column operands in lane order
+// (lane = n % 32 + 32 * ((k % 16) / 8), 8 consecutive k per lane).  Chunk-major order makes all
+// workgroups that advance through K in step sweep HBM contiguously; a strip-major order puts
+// every wave's stream at a multiple of K * 64 bytes and piles them onto a few memory channels.
 // =============================================================================================
 __global__ void repack_weight_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ Wu,
                                      bf16_t* __restrict__ Wp, int N, int K, int interleave16) {
   size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  size_t total = (size_t)(N / 32) * (K / 16) * 64;
+  const int NB = N / 32;
+  size_t total = (size_t)NB * (K / 16) * 64;
   if (t >= total) return;
   int lane = (int)(t & 63);
-  size_t blk = t >> 6;
-  int kb = (int)(blk % (K / 16));
-  int nb = (int)(blk / (K / 16));
+  size_t blk = t >> 6;                 // ((chunk * NB + strip) * 4 + k-block in chunk)
+  int kb4 = (int)(blk & 3);
+  size_t cell = blk >> 2;
+  int nb = (int)(cell % NB);
+  int chunk = (int)(cell / NB);
   int n = nb * 32 + (lane & 31);
-  int k = kb * 16 + (lane >> 5) * 8;
+  int k = chunk * 64 + kb4 * 16 + (lane >> 5) * 8;
   const bf16_t* src;
   if (interleave16) {
     int grp = n >> 4;                       // even groups: gate rows, odd groups: up rows
@@ -39,27 +43,32 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 }
 
 // =============================================================================================
-// GEMM  C[M,N] = A[M,K] * W[N,K]^T.  Workgroup = 4 waves, tile 128 rows x 128 columns; wave w owns
-// the 32-column strip 4*blockIdx.x + w for all 128 rows (4 accumulators of 32x32).  Per 64-k chunk
-// the A tile (16 KB, already in operand order in HBM) is copied to LDS and shared by the waves;
-// each wave streams its own weight strip straight from HBM into registers, one chunk ahead.
-// blockIdx.z selects a K-slice (split-K, results combined with fp32 atomics).
+// GEMM  C[M,N] = A[M,K] * W[N,K]^T for weight streaming.  Workgroup = NW waves (2 or 4), tile
+// 128 rows x 32*NW columns; wave w owns the 32-column strip NW*blockIdx.x + w for all 128 rows
+// (4 accumulators of 32x32).  Per 64-k chunk the A tile (16 KB, already in operand order in HBM)
+// is copied to LDS and shared by the waves; each wave streams its own weight cells straight from
+// HBM into registers, D chunks ahead.  blockIdx.z selects a K-slice (split-K); every slice
+// stores its own fp32 partial sum, which the consumer kernel adds in a fixed order (no atomics:
+// results are bit-reproducible).
 // =============================================================================================
-template <int EPI, int D>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
-                                                        const bf16_t* __restrict__ Wp,
-                                                        void* __restrict__ Cv, int M, int N, int K,
-                                                        int chunks_per_split) {
+template <int EPI, int D, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
+                                                            const bf16_t* __restrict__ Wp,
+                                                            void* __restrict__ Cv, int M, int N,
+                                                            int K, int chunks_per_split) {
+  constexpr int NT = 64 * NW;        // threads
+  constexpr int APT = 1024 / NT;     // 16-byte pieces of an A chunk per thread
   __shared__ u32x4 As[2][1024];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int nb = blockIdx.x * 4 + wave;
+  const int nb = blockIdx.x * NW + wave;
   const bool active = nb * 32 < N;
   const int mt = blockIdx.y;
   const int nchunks = K >> 6;
   const int c0 = blockIdx.z * chunks_per_split;
   const int c1 = min(c0 + chunks_per_split, nchunks);
   const u32x4* Ag = (const u32x4*)(A + (size_t)mt * K * 128);       // tile: 128 rows x K
-  const u32x4* Wg = (const u32x4*)(Wp + (size_t)(active ? nb : 0) * K * 32);  // strip: 32 columns x K
+  const int NB = N >> 5;
+  const u32x4* Wg = (const u32x4*)Wp + (size_t)(active ? nb : 0) * 256;   // cell (chunk 0, strip nb)
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; i++)
@@ -70,36 +79,35 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
   // that the pipeline has no conditional register definitions.  Stages are spelled out (no
   // arrays of stages) so that every buffer lives in registers.
   const int clast = c1 - 1;
-  u32x4 a0[4], a1[4], a2[4], a3[4], b0[4], b1[4], b2[4], b3[4];
+  u32x4 a0[APT], a1[APT], a2[APT], a3[APT], b0[4], b1[4], b2[4], b3[4];
 #define GEMM_LOAD(AR, BR, CHUNK)                                            \
   {                                                                         \
     const int cl_ = min((CHUNK), clast);                                    \
-    _Pragma("unroll") for (int i = 0; i < 4; i++) {                         \
-      AR[i] = Ag[(size_t)cl_ * 1024 + i * 256 + tid];                       \
-      BR[i] = Wg[(size_t)(cl_ * 4 + i) * 64 + lane];                        \
-    }                                                                       \
+    _Pragma("unroll") for (int i = 0; i < APT; i++)                         \
+      AR[i] = Ag[(size_t)cl_ * 1024 + i * NT + tid];                        \
+    _Pragma("unroll") for (int i = 0; i < 4; i++)                           \
+      BR[i] = Wg[((size_t)cl_ * NB * 4 + i) * 64 + lane];                   \
+    /* keep the scheduler from sinking these loads towards their use */     \
+    __builtin_amdgcn_sched_barrier(0);                                      \
   }
 #define GEMM_STAGE(S, AR, BR)                                               \
   if ((S) < D) {                                                            \
     const int cc = c + (S);                                                 \
     u32x4* buf = As[(S) & 1];                                               \
+    /* past the end of the slice the weight operand is zeroed: the body stays branch free; \
+       the masked copy also frees the staging registers before they are refilled */ \
+    const unsigned keep = cc < c1 ? 0xffffffffu : 0u;                       \
     u32x4 bcur[4];                                                          \
-    _Pragma("unroll") for (int i = 0; i < 4; i++) {                         \
-      buf[i * 256 + tid] = AR[i];                                           \
-      bcur[i] = BR[i];                                                      \
-    }                                                                       \
+    _Pragma("unroll") for (int i = 0; i < APT; i++) buf[i * NT + tid] = AR[i]; \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) bcur[i] = BR[i] & keep;   \
+    __builtin_amdgcn_sched_barrier(0);                                      \
     __syncthreads();                                                        \
     GEMM_LOAD(AR, BR, cc + D)                                               \
-    {                                                                       \
-      /* past the end of the slice the weight operand is zeroed: the body stays branch free */ \
-      const unsigned keep = cc < c1 ? 0xffffffffu : 0u;                     \
-      _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                    \
-        u32x4 bm = bcur[kk] & keep;                                         \
-        bf16x8 b = __builtin_bit_cast(bf16x8, bm);                          \
-        _Pragma("unroll") for (int mb = 0; mb < 4; mb++) {                  \
-          bf16x8 a = __builtin_bit_cast(bf16x8, buf[(kk * 4 + mb) * 64 + lane]); \
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0); \
-        }                                                                   \
+    _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                      \
+      bf16x8 b = __builtin_bit_cast(bf16x8, bcur[kk]);                      \
+      _Pragma("unroll") for (int mb = 0; mb < 4; mb++) {                    \
+        bf16x8 a = __builtin_bit_cast(bf16x8, buf[(kk * 4 + mb) * 64 + lane]); \
+        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0); \
       }                                                                     \
     }                                                                       \
   }
@@ -119,6 +127,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
 #undef GEMM_STAGE
   if (!active) return;
   const int col = nb * 32 + (lane & 31);
+  float* Cp = (float*)Cv + (size_t)blockIdx.z * M * N;
 #pragma unroll
   for (int mb = 0; mb < 4; mb++) {
 #pragma unroll
@@ -133,40 +142,42 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
           ((bf16_t*)Cv)[atile_off(row, j, N >> 1)] = f2bf(y);
         }
       } else if (row < M) {
-        float* c = (float*)Cv + (size_t)row * N + col;
-        if (EPI == EPI_ATOMIC_ADD) unsafeAtomicAdd(c, v);
-        else *c = v;
+        Cp[(size_t)row * N + col] = v;
       }
     }
   }
 }
 
-int g_gemm_depth = 4;   // chunks in flight per workgroup (tuning knob)
-
-template <int D>
-static void gemm_launch_d(hipStream_t s, dim3 grid, const bf16_t* A, const bf16_t* Wp, void* C, int M,
-                          int N, int K, int epilogue, int cps) {
+template <int D, int NW>
+static void gemm_launch(hipStream_t s, dim3 grid, const bf16_t* A, const bf16_t* Wp, void* C, int M,
+                        int N, int K, int epilogue, int cps) {
   if (epilogue == EPI_STORE)
-    gemm_mfma_kernel<EPI_STORE, D><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
-  else if (epilogue == EPI_ATOMIC_ADD)
-    gemm_mfma_kernel<EPI_ATOMIC_ADD, D><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+    gemm_mfma_kernel<EPI_STORE, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps);
   else
-    gemm_mfma_kernel<EPI_SWIGLU, D><<<grid, 256, 0, s>>>(A, Wp, C, M, N, K, cps);
+    gemm_mfma_kernel<EPI_SWIGLU, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps);
 }
 
-void launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
-                      int K, int epilogue, int splits) {
-  if (M <= 0) return;
+// depth = chunks in flight per workgroup (2 or 4)
+int launch_gemm_mfma_cfg(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
+                         int K, int epilogue, int splits, int nw, int depth) {
+  if (M <= 0) return 0;
   int nchunks = K / 64;
-  if (splits < 1) splits = 1;
+  if (splits < 1 || epilogue == EPI_SWIGLU) splits = 1;
   if (splits > nchunks) splits = nchunks;
   int cps = (nchunks + splits - 1) / splits;
   splits = (nchunks + cps - 1) / cps;
-  dim3 grid((N + 127) / 128, (M + 127) / 128, splits);
-  switch (g_gemm_depth) {
-    case 2: gemm_launch_d<2>(s, grid, A, Wp, C, M, N, K, epilogue, cps); break;
-    default: gemm_launch_d<4>(s, grid, A, Wp, C, M, N, K, epilogue, cps); break;
-  }
+  dim3 grid((N + 32 * nw - 1) / (32 * nw), (M + 127) / 128, splits);
+  if (nw == 2 && depth == 2) gemm_launch<2, 2>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  else if (nw == 2) gemm_launch<4, 2>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  else if (depth == 2) gemm_launch<2, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  else gemm_launch<4, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  return splits;
+}
+
+int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
+                     int K, int epilogue, int splits, int nw) {
+  // two chunks in flight: fewer registers, more resident workgroups (measured best at M = 128)
+  return launch_gemm_mfma_cfg(s, A, Wp, C, M, N, K, epilogue, splits, nw, 2);
 }
 
 // =============================================================================================
@@ -212,8 +223,12 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   __shared__ float s_acc[4 * 16 * 128];
   __shared__ float s_m[4 * 16];
   __shared__ float s_l[4 * 16];
-  const AttnItem it = items[blockIdx.x];
-  const int kvh = blockIdx.y, split = blockIdx.z, nsplit = gridDim.z;
+  // blockIdx.x = item * nkv + kvh: consecutive workgroups go round-robin to the 8 XCDs, so with
+  // kv head fastest all trajectories of one kv head share an XCD (for nkv = 8) and trajectories
+  // that share prompt pages (a forked group, adjacent items) find each other's pages in that L2.
+  const int item_idx = blockIdx.x / nkv;
+  const AttnItem it = items[item_idx];
+  const int kvh = blockIdx.x - item_idx * nkv, split = blockIdx.y, nsplit = gridDim.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, n = lane & 15, r = n >> gshift, hq = n & ((1 << gshift) - 1);
   const bool colvalid = r < it.nrows;
@@ -322,7 +337,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
           make_uint4(w[0], w[1], w[2], w[3]);
     }
   } else {
-    float* dst = scratch + (((size_t)blockIdx.x * nkv + kvh) * nsplit + split) * (16 * 130);
+    float* dst = scratch + (((size_t)item_idx * nkv + kvh) * nsplit + split) * (16 * 130);
 #pragma unroll
     for (int e = 0; e < 8; e++) dst[cn * 128 + d0 + e] = o8[e];
     if ((tid & 15) == 0) { dst[16 * 128 + cn] = mt; dst[16 * 128 + 16 + cn] = L; }
@@ -361,7 +376,7 @@ void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const At
   float scale2 = 1.4426950408889634f / sqrtf((float)md.d);
   int gshift = 0;
   while ((1 << gshift) < md.nq / md.nkv) gshift++;
-  dim3 grid(n_items, md.nkv, splits);
+  dim3 grid(n_items * md.nkv, splits);
   attention_mfma_kernel<<<grid, 256, 0, s>>>(q, (const bf16_t*)pool.k, (const bf16_t*)pool.v, items,
                                              page_table, o, scratch, md.nq, md.nkv, gshift,
                                              md.max_pages_per_traj, scale2);
