@@ -54,8 +54,19 @@ __global__ void add_rmsnorm_kernel(float* __restrict__ h, const float* __restric
   float ss = 0.f;
   for (int j = threadIdx.x * 4; j < H; j += 1024) {
     float4 v = *(const float4*)(x + j);
-    for (int p = 0; p < n_part; p++) {
-      float4 u = *(const float4*)(pr + p * part_stride + j);
+    int p = 0;
+    for (; p + 4 <= n_part; p += 4) {     // four independent loads in flight, added in order
+      float4 u0 = *(const float4*)(pr + (size_t)p * part_stride + j);
+      float4 u1 = *(const float4*)(pr + (size_t)(p + 1) * part_stride + j);
+      float4 u2 = *(const float4*)(pr + (size_t)(p + 2) * part_stride + j);
+      float4 u3 = *(const float4*)(pr + (size_t)(p + 3) * part_stride + j);
+      v.x = (((v.x + u0.x) + u1.x) + u2.x) + u3.x;
+      v.y = (((v.y + u0.y) + u1.y) + u2.y) + u3.y;
+      v.z = (((v.z + u0.z) + u1.z) + u2.z) + u3.z;
+      v.w = (((v.w + u0.w) + u1.w) + u2.w) + u3.w;
+    }
+    for (; p < n_part; p++) {
+      float4 u = *(const float4*)(pr + (size_t)p * part_stride + j);
       v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
     }
     if (n_part > 0) *(float4*)(x + j) = v;
