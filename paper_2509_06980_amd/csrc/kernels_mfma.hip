@@ -103,10 +103,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
     __builtin_amdgcn_sched_barrier(0);                                      \
     __syncthreads();                                                        \
     GEMM_LOAD(AR, BR, cc + D)                                               \
+    /* all 16 row operands of the chunk are requested from LDS before the first MFMA: with one \
+       wave per SIMD nothing else hides the LDS latency */                  \
+    u32x4 av[16];                                                           \
+    _Pragma("unroll") for (int i = 0; i < 16; i++) av[i] = buf[i * 64 + lane]; \
+    __builtin_amdgcn_sched_barrier(0);                                      \
     _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                      \
       bf16x8 b = __builtin_bit_cast(bf16x8, bcur[kk]);                      \
       _Pragma("unroll") for (int mb = 0; mb < 4; mb++) {                    \
-        bf16x8 a = __builtin_bit_cast(bf16x8, buf[(kk * 4 + mb) * 64 + lane]); \
+        bf16x8 a = __builtin_bit_cast(bf16x8, av[kk * 4 + mb]);             \
         acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0); \
       }                                                                     \
     }                                                                       \

@@ -56,6 +56,10 @@ SHAPES = {
     "tiny-bf16": ModelShape(2, 256, 4, 2, 64, 688, 4096, weight_dtype=1),
     # head_dim 128 / widths that are multiples of the MFMA tiles, still small
     "small-d128": ModelShape(3, 512, 8, 2, 128, 1024, 8192, weight_dtype=1),
+    # other GQA group sizes for the MFMA attention kernel (group = n_q / n_kv)
+    "small-g2": ModelShape(2, 256, 4, 2, 128, 512, 4096, weight_dtype=1),
+    "small-g1": ModelShape(2, 256, 2, 2, 128, 512, 4096, weight_dtype=1),
+    "small-g8": ModelShape(2, 256, 8, 1, 128, 512, 4096, weight_dtype=1),
     "qwen3-0.6b": ModelShape(28, 1024, 16, 8, 128, 3072, 151936),
     "qwen3-4b": ModelShape(36, 2560, 32, 8, 128, 9728, 151936),
     "qwen3-8b": ModelShape(36, 4096, 32, 8, 128, 12288, 151936),

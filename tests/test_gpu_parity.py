@@ -91,7 +91,8 @@ def _bf16_workload(vocab):
     return uniform_turns("bf16-small", vocab, 6, 45, 2, 7, 21, 1.0, group_size=3, final_release=False)
 
 
-@pytest.mark.parametrize("name,flags", [("tiny-bf16", 0), ("small-d128", 1), ("small-d128", 0)])
+@pytest.mark.parametrize("name,flags", [("tiny-bf16", 0), ("small-d128", 1), ("small-d128", 0),
+                                        ("small-g2", 0), ("small-g1", 0), ("small-g8", 0)])
 def test_bf16_lockstep(name, flags):
     shape = SHAPES[name]
     blob = make_weight_blob(shape, seed=2, weight_std=0.03, gain_std=0.1)
