@@ -77,7 +77,6 @@ struct rl_model {
   int32_t *d_ids = nullptr, *h_ids = nullptr;
   float *d_lp = nullptr, *h_lp = nullptr;
   uint8_t* d_mask = nullptr;
-  int max_attn_splits = 16;
   // host state
   std::unordered_map<int32_t, Traj> traj;
   std::vector<int> free_slots;
@@ -148,7 +147,8 @@ struct RowMeta {
   const int32_t *tok, *pos, *slot;
   const AttnItem* items;
   int n_items;
-  int attn_splits;
+  const AttnMerge* merges;
+  int n_merges;
   double kv_bytes;   // keys + values the attention of one layer has to read
   bool time_attn;
 };
@@ -211,8 +211,8 @@ void forward_mfma(rl_model* m, int M, const RowMeta& r) {
                                                 (const bf16_t*)w.gk, m->rope_cs, r.pos, r.slot,
                                                 m->page_table, (bf16_t*)m->qb, m->pools[l], md, M);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
-    launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, m->page_table,
-                          (bf16_t*)m->xo, m->attn_scratch, md, r.attn_splits);
+    launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, r.merges, r.n_merges,
+                          m->page_table, (bf16_t*)m->xo, m->attn_scratch, md);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
     GemmPlan po = plan_gemm(M, H, qw, true);
     int so = launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->ph, M, H, qw, EPI_STORE,
@@ -263,22 +263,24 @@ void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done) {
 // ---- per-call metadata staging ----------------------------------------------------------------
 // Layout of the integer staging buffer for a pass over M rows:
 //   [0,M) tok  [M,2M) pos  [2M,3M) slot  [3M,4M) traj id  [4M,5M) index of the new token
-//   [5M,6M) forced / target ids  [6M, 6M + 4 * n_items) attention items
+//   [5M,6M) forced / target ids  [6M, ...) attention items (8 ints each), then merge records (4)
 struct Staging {
   std::vector<int32_t> tok, pos, slot, traj, newpos, forced;
   std::vector<AttnItem> items;
+  std::vector<AttnMerge> merges;
   std::vector<uint8_t> mask;
-  void clear() { tok.clear(); pos.clear(); slot.clear(); traj.clear(); newpos.clear(); forced.clear(); items.clear(); mask.clear(); }
+  void clear() { tok.clear(); pos.clear(); slot.clear(); traj.clear(); newpos.clear(); forced.clear(); items.clear(); merges.clear(); mask.clear(); }
 };
 
 struct DevMeta {
   int32_t *tok, *pos, *slot, *traj, *newpos, *forced;
   AttnItem* items;
+  AttnMerge* merges;
 };
 
 int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   size_t M = st.tok.size();
-  size_t need = 6 * M + 4 * st.items.size();
+  size_t need = 6 * M + 8 * st.items.size() + 4 * st.merges.size();
   if (need > m->meta_ints) return fail(RL_E_ARG, "internal: metadata staging too small");
   int32_t* h = m->h_meta;
   auto put = [&](const std::vector<int32_t>& v, size_t at) {
@@ -287,10 +289,13 @@ int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   put(st.tok, 0); put(st.pos, M); put(st.slot, 2 * M); put(st.traj, 3 * M); put(st.newpos, 4 * M);
   put(st.forced, 5 * M);
   if (!st.items.empty()) memcpy(h + 6 * M, st.items.data(), st.items.size() * sizeof(AttnItem));
+  if (!st.merges.empty())
+    memcpy(h + 6 * M + 8 * st.items.size(), st.merges.data(), st.merges.size() * sizeof(AttnMerge));
   HIPCHECK(hipMemcpyAsync(m->d_meta, h, need * 4, hipMemcpyHostToDevice, m->stream));
   dm->tok = m->d_meta; dm->pos = m->d_meta + M; dm->slot = m->d_meta + 2 * M;
   dm->traj = m->d_meta + 3 * M; dm->newpos = m->d_meta + 4 * M; dm->forced = m->d_meta + 5 * M;
   dm->items = (AttnItem*)(m->d_meta + 6 * M);
+  dm->merges = (AttnMerge*)(m->d_meta + 6 * M + 8 * st.items.size());
   if (!st.mask.empty())
     HIPCHECK(hipMemcpyAsync(m->d_mask, st.mask.data(), st.mask.size(), hipMemcpyHostToDevice, m->stream));
   return RL_OK;
@@ -336,19 +341,37 @@ int check_ids(const int32_t* ids, int32_t n) {
 }
 
 // attention work items for `cnt` consecutive rows of one trajectory starting at batch row row0
+// (chunked prefill: every item covers all pages up to its last row, one part)
 void add_items(rl_model* m, Staging& st, int row0, int cnt, int slot, int pos0) {
   int R = m->rows_per_item;
-  for (int a = 0; a < cnt; a += R)
-    st.items.push_back(AttnItem{row0 + a, std::min(R, cnt - a), slot, pos0 + a});
+  for (int a = 0; a < cnt; a += R) {
+    int nr = std::min(R, cnt - a);
+    st.items.push_back(AttnItem{row0 + a, nr, slot, pos0 + a, 0, (pos0 + a + nr - 1) / RL_PAGE + 1, -1, 0});
+  }
 }
 
-int pick_attn_splits(rl_model* m, int n_items, int max_pos) {
-  if (!m->mfma || n_items > m->rt.max_trajectories) return 1;
-  int waves = n_items * m->md.nkv * 4;
-  int want = (4096 + waves - 1) / waves;
-  int pages = max_pos / RL_PAGE + 1;
-  int cap = std::max(1, pages / 16);         // at least ~4 pages per wave
-  return std::max(1, std::min({want, cap, m->max_attn_splits}));
+// Decode items: one row per trajectory.  Contexts are cut into parts of about equal page count so
+// that ~kAttnTargetWgs workgroups share the keys / values evenly whatever the mix of lengths; a
+// part never gets fewer than 16 pages.
+const int kAttnTargetWgs = 1024;
+void add_decode_items(rl_model* m, Staging& st) {
+  int n = (int)st.pos.size();
+  int64_t total_pages = 0;
+  for (int i = 0; i < n; i++) total_pages += st.pos[i] / RL_PAGE + 1;
+  int chunk = (int)std::max<int64_t>(16, (total_pages * m->md.nkv + kAttnTargetWgs - 1) / kAttnTargetWgs);
+  int next_part = 0;
+  for (int i = 0; i < n; i++) {
+    int np = st.pos[i] / RL_PAGE + 1;
+    int parts = m->mfma ? (np + chunk - 1) / chunk : 1;
+    if (parts <= 1) {
+      st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], 0, np, -1, 0});
+      continue;
+    }
+    int per = (np + parts - 1) / parts;
+    st.merges.push_back(AttnMerge{i, next_part, parts, 0});
+    for (int k = 0; k < parts; k++)
+      st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], k * per, std::min((k + 1) * per, np), next_part++, 0});
+  }
 }
 
 // Chunked prefill of tokens[n_cached .. upto) for the listed trajectories (upto given per traj).
@@ -382,7 +405,7 @@ int prefill(rl_model* m, const std::vector<std::pair<Traj*, int>>& work) {
     DevMeta dm;
     int rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), 1, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, 0.0, false};
     forward_rows(m, M, r);
     HIPCHECK(hipGetLastError());
     HIPCHECK(hipStreamSynchronize(m->stream));
@@ -436,10 +459,10 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
     st.traj.push_back(ids[i]);
     st.newpos.push_back(nt);
     if (forced) st.forced.push_back(forced[i]);
-    st.items.push_back(AttnItem{i, 1, t->slot, nt - 1});
     max_pos = std::max(max_pos, nt - 1);
     kvb += (double)nt * 2.0 * m->md.nkv * m->md.d * m->el;
   }
+  add_decode_items(m, st);
   DevMeta dm;
   rc = upload_meta(m, st, &dm);
   if (rc) return rc;
@@ -460,7 +483,7 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
       }
     }
   }
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, n, pick_attn_splits(m, n, max_pos), kvb, timed};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), kvb, timed};
   forward_rows(m, n, r);
   lm_head_rows(m, n, 0, n, false);
   bool greedy = temperature == 0.0f;
@@ -630,8 +653,8 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   if (!m->mfma) TRY(m->dalloc((void**)&m->gu, Mc * 2 * I * 4, true));
   TRY(m->dalloc((void**)&m->logits, (size_t)m->Rl * V * 4));
   if (m->mfma)
-    TRY(m->dalloc((void**)&m->attn_scratch,
-                  (size_t)rt->max_trajectories * c.n_kv_heads * m->max_attn_splits * 16 * 130 * 4));
+    TRY(m->dalloc((void**)&m->attn_scratch,   // one slot per part of a cut decode row
+                  (size_t)(kAttnTargetWgs / c.n_kv_heads + 2 * rt->max_trajectories + 64) * c.n_kv_heads * 16 * 130 * 4));
   int nseg = sampler_nseg(V);
   TRY(m->dalloc((void**)&m->ss.segmax, (size_t)m->Rl * nseg * 4));
   TRY(m->dalloc((void**)&m->ss.segarg, (size_t)m->Rl * nseg * 4));
@@ -640,7 +663,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc((void**)&m->d_ids, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_lp, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_mask, Mc));
-  m->meta_ints = 10 * Mc + 3 * 65536;
+  m->meta_ints = 32 * Mc + 3 * 65536;
   TRY(m->dalloc((void**)&m->d_meta, m->meta_ints * 4));
   HIPTRY(hipHostMalloc((void**)&m->h_meta, m->meta_ints * 4));
   HIPTRY(hipHostMalloc((void**)&m->h_ids, (size_t)m->Rl * 4));
@@ -834,11 +857,11 @@ extern "C" int rl_debug_logits(rl_model* m, int32_t id, float* logits_out) {
   st.tok.push_back(t.tokens[nt - 1]);
   st.pos.push_back(nt - 1);
   st.slot.push_back(t.slot);
-  st.items.push_back(AttnItem{0, 1, t.slot, nt - 1});
+  add_decode_items(m, st);
   DevMeta dm;
   int rc = upload_meta(m, st, &dm);
   if (rc) return rc;
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, 1, pick_attn_splits(m, 1, nt - 1), 0.0, false};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), 0.0, false};
   forward_rows(m, 1, r);   // rewrites the key / value of position nt-1 with the same values
   lm_head_rows(m, 1, 0, 1, false);
   HIPCHECK(hipGetLastError());
@@ -897,7 +920,7 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
     DevMeta dm;
     rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), 1, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, 0.0, false};
     forward_rows(m, M, r);
     for (int r0 = 0; r0 < M; r0 += m->Rl) {
       int R = std::min(m->Rl, M - r0);

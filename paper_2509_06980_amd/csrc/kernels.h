@@ -5,13 +5,23 @@
 
 #include "rl_common.h"
 
-// One attention work item: up to 4 consecutive batch rows of one trajectory that share a
-// pass over its cached context (decode: one row; chunked prefill: 4 rows).
+// One attention work item: up to 16 / (n_q / n_kv) consecutive batch rows of one trajectory and
+// a range of its pages.  Decode: one row; long contexts are cut into several items ("parts") so
+// that workgroups carry similar amounts of keys / values whatever the mix of context lengths.
+// Chunked prefill: several rows, always one part.
 struct AttnItem {
-  int32_t row0;   // first batch row
-  int32_t nrows;  // 1..4
-  int32_t slot;   // trajectory slot (row of the page table)
-  int32_t pos0;   // position of row0; row r sits at pos0 + r and sees positions <= pos0 + r
+  int32_t row0;    // first batch row
+  int32_t nrows;   // rows in this item
+  int32_t slot;    // trajectory slot (row of the page table)
+  int32_t pos0;    // position of row0; row r sits at pos0 + r and sees positions <= pos0 + r
+  int32_t pg_lo;   // pages [pg_lo, pg_hi) of the trajectory are this item's share
+  int32_t pg_hi;
+  int32_t part;    // >= 0: partial result goes to scratch slot `part`; -1: the item is complete
+  int32_t pad;
+};
+// Rows whose attention was cut into parts: merge scratch slots [first, first + nparts).
+struct AttnMerge {
+  int32_t row, first, nparts, pad;
 };
 
 struct KvPool {      // one layer
@@ -78,10 +88,11 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
                           int K, bool interleave16);
 
 // paged GQA attention over work items; q bf16 row-major [M, nq*128]; o bf16 A-tile [.., nq*128].
-// scratch: fp32 [n_items * nkv * splits * 16 * 130] when splits > 1.
+// scratch: fp32 [part slots][nkv][16 * 130] for items with part >= 0, merged by `merges`.
 void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
-                           int n_items, const int32_t* page_table, bf16_t* o, float* scratch,
-                           const ModelDims& md, int splits);
+                           int n_items, const AttnMerge* merges, int n_merges,
+                           const int32_t* page_table, bf16_t* o, float* scratch,
+                           const ModelDims& md);
 
 // ---- sampler ---------------------------------------------------------------------------------
 struct SamplerScratch {

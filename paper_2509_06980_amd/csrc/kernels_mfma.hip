@@ -193,8 +193,9 @@ int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, 
 // Per 16-token page:  S^T[token, n] = K[token, :] . Q[n, :]   (4 x mfma 16x16x32, K straight from
 // the page in operand order), online softmax per column, O^T[d, n] += V^T[d, token] P^T[token, n]
 // (8 x mfma 16x16x16; the score accumulator layout is exactly the P operand layout).
-// Waves split the pages; partial (max, sum, O) are merged in fixed order through LDS and, when the
-// context is split over several workgroups, through a scratch buffer and a second kernel.
+// The item's page range is split over the 4 waves; partial (max, sum, O) are merged in fixed order
+// through LDS and, when a row's context was cut into several items, through a scratch buffer and a
+// second kernel.
 // =============================================================================================
 #define ATT_NEG (-1.0e30f)
 
@@ -233,15 +234,13 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   // that share prompt pages (a forked group, adjacent items) find each other's pages in that L2.
   const int item_idx = blockIdx.x / nkv;
   const AttnItem it = items[item_idx];
-  const int kvh = blockIdx.x - item_idx * nkv, split = blockIdx.y, nsplit = gridDim.y;
+  const int kvh = blockIdx.x - item_idx * nkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, n = lane & 15, r = n >> gshift, hq = n & ((1 << gshift) - 1);
   const bool colvalid = r < it.nrows;
   const int mypos = it.pos0 + r;
-  const int n_pages = (it.pos0 + it.nrows - 1) / RL_PAGE + 1;
-  const int nparts = nsplit * 4, part = split * 4 + wave;
-  const int per = (n_pages + nparts - 1) / nparts;
-  const int pg0 = part * per, pg1 = min(pg0 + per, n_pages);
+  const int per = (it.pg_hi - it.pg_lo + 3) >> 2;
+  const int pg0 = it.pg_lo + wave * per, pg1 = min(pg0 + per, it.pg_hi);
   const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
 
   uint4 qreg[4];
@@ -331,7 +330,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   float mt, L, o8[8];
   attn_merge_store(s_m, s_l, s_acc, 4, 16, 16 * 128, cn, d0, &mt, &L, o8);
   const int cr = cn >> gshift, chq = cn & ((1 << gshift) - 1);
-  if (nsplit == 1) {
+  if (it.part < 0) {
     if (cr < it.nrows) {
       float inv = 1.0f / L;
       uint32_t w[4];
@@ -342,50 +341,51 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
           make_uint4(w[0], w[1], w[2], w[3]);
     }
   } else {
-    float* dst = scratch + (((size_t)item_idx * nkv + kvh) * nsplit + split) * (16 * 130);
+    float* dst = scratch + ((size_t)it.part * nkv + kvh) * (16 * 130);
 #pragma unroll
     for (int e = 0; e < 8; e++) dst[cn * 128 + d0 + e] = o8[e];
     if ((tid & 15) == 0) { dst[16 * 128 + cn] = mt; dst[16 * 128 + 16 + cn] = L; }
   }
 }
 
-// grid (n_items, nkv), block 256: merge the context splits of one (item, kv head)
+// grid (n_merges, nkv), block 256: merge the parts of one (row, kv head) in ascending order
 __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ scratch,
-                                                              const AttnItem* __restrict__ items,
+                                                              const AttnMerge* __restrict__ merges,
                                                               bf16_t* __restrict__ o, int nq,
-                                                              int nkv, int gshift, int nsplit) {
-  const AttnItem it = items[blockIdx.x];
+                                                              int nkv, int gshift) {
+  const AttnMerge mg = merges[blockIdx.x];
   const int kvh = blockIdx.y, tid = threadIdx.x;
-  const float* src = scratch + (((size_t)blockIdx.x * nkv + kvh) * nsplit) * (16 * 130);
+  const float* src = scratch + ((size_t)mg.first * nkv + kvh) * (16 * 130);
+  const size_t stride = (size_t)nkv * (16 * 130);
   const int cn = tid >> 4, d0 = (tid & 15) * 8;
   float mt, L, o8[8];
-  attn_merge_store(src + 16 * 128, src + 16 * 128 + 16, src, nsplit, 16 * 130, 16 * 130, cn, d0, &mt,
+  attn_merge_store(src + 16 * 128, src + 16 * 128 + 16, src, mg.nparts, stride, stride, cn, d0, &mt,
                    &L, o8);
   const int cr = cn >> gshift, chq = cn & ((1 << gshift) - 1);
-  if (cr < it.nrows) {
+  if (cr == 0) {   // cut rows are decode rows: one query row per item
     float inv = 1.0f / L;
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 4; e++)
       w[e] = (uint32_t)f2bf(o8[2 * e] * inv) | ((uint32_t)f2bf(o8[2 * e + 1] * inv) << 16);
-    *(uint4*)(o + atile_off(it.row0 + cr, ((kvh << gshift) + chq) * 128 + d0, nq * 128)) =
+    *(uint4*)(o + atile_off(mg.row, ((kvh << gshift) + chq) * 128 + d0, nq * 128)) =
         make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
 void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
-                           int n_items, const int32_t* page_table, bf16_t* o, float* scratch,
-                           const ModelDims& md, int splits) {
+                           int n_items, const AttnMerge* merges, int n_merges,
+                           const int32_t* page_table, bf16_t* o, float* scratch,
+                           const ModelDims& md) {
   if (n_items <= 0) return;
-  if (splits < 1) splits = 1;
   float scale2 = 1.4426950408889634f / sqrtf((float)md.d);
   int gshift = 0;
   while ((1 << gshift) < md.nq / md.nkv) gshift++;
-  dim3 grid(n_items * md.nkv, splits);
-  attention_mfma_kernel<<<grid, 256, 0, s>>>(q, (const bf16_t*)pool.k, (const bf16_t*)pool.v, items,
-                                             page_table, o, scratch, md.nq, md.nkv, gshift,
-                                             md.max_pages_per_traj, scale2);
-  if (splits > 1)
-    attention_merge_kernel<<<dim3(n_items, md.nkv), 256, 0, s>>>(scratch, items, o, md.nq, md.nkv,
-                                                                 gshift, splits);
+  attention_mfma_kernel<<<n_items * md.nkv, 256, 0, s>>>(q, (const bf16_t*)pool.k,
+                                                        (const bf16_t*)pool.v, items, page_table, o,
+                                                        scratch, md.nq, md.nkv, gshift,
+                                                        md.max_pages_per_traj, scale2);
+  if (n_merges > 0)
+    attention_merge_kernel<<<dim3(n_merges, md.nkv), 256, 0, s>>>(scratch, merges, o, md.nq, md.nkv,
+                                                                  gshift);
 }
