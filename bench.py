@@ -29,6 +29,23 @@ CONFIGS = {
 HBM_PEAK_GBS = 8000.0
 
 
+def recorded_traffic(config):
+    """HBM bytes per decode-attention launch from the committed rocprofv3 counter summary, or None
+    when there is none for this workload or the kernel source changed since it was taken."""
+    import re
+    from bench_counters import kernel_source_hash
+    path = os.path.join(ROOT, "profiles", f"attention_mfma_{config}_hbm_counters.md")
+    try:
+        txt = open(path).read()
+        t = re.search(r"traffic_bytes_per_launch: (\d+)", txt)
+        h = re.search(r"kernel_source_sha256_16: (\w+)", txt)
+        if t and h and h.group(1) == kernel_source_hash():
+            return int(t.group(1))
+    except OSError:
+        pass
+    return None
+
+
 def run_rollout(engine, w, shape, stats):
     """Replay the workload once (free-running sampling); returns generated token count."""
     kvtok = shape.kv_bytes_per_token()
@@ -155,7 +172,8 @@ def main():
         # shared by a forked group are needed once); the per-trajectory count is kept beside it
         achieved = attn_unique / (attn_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": recorded_traffic(args.config) if args.scale == 1.0 else None,
                     "achieved_counting_shared_pages_per_trajectory": round(attn_bytes / (attn_ms * 1e-3) / 1e9, 1),
                     "kernel": "attention_mfma_kernel" if eng.config["head_dim"] == 128 and
                     eng.config["weight_dtype"] == 1 else "attention_generic_kernel",

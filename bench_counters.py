@@ -1,0 +1,90 @@
+#!/usr/bin/env python3
+"""Summarise rocprofv3 counter runs of bench.py for the decode-attention kernel.
+
+Usage (after the two counter runs named in the summary it writes):
+    python bench_counters.py FETCH.csv WRITE.csv [STATS.csv] > profiles/<name>.md
+
+FETCH.csv / WRITE.csv are rocprofv3 `--pmc FETCH_SIZE` / `--pmc WRITE_SIZE` counter_collection
+files (KiB per dispatch).  Both counters are calibrated against the largest device-to-device
+copy of the run (the embedding table that rl_model_load copies: vocab x hidden x 2 bytes read
+and written once).  Prints a markdown summary whose `traffic_bytes_per_launch` line bench.py
+reads back, together with the hash of the kernel source the counters belong to.
+"""
+import csv
+import hashlib
+import os
+import sys
+from collections import defaultdict
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+KERNEL_SRC = os.path.join(ROOT, "paper_2509_06980_amd", "csrc", "kernels_mfma.hip")
+
+
+def kernel_source_hash():
+    return hashlib.sha256(open(KERNEL_SRC, "rb").read()).hexdigest()[:16]
+
+
+def read_counter(path, counter):
+    """-> {kernel name: {grid size: [values]}}"""
+    out = defaultdict(lambda: defaultdict(list))
+    with open(path, newline="") as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            out[r["Kernel_Name"].split("(")[0]][int(r["Grid_Size"])].append(float(r["Counter_Value"]))
+    return out
+
+
+def trace_summary(path):
+    """Average duration of attention_mfma_kernel per grid size from a rocprofv3 kernel trace CSV
+    (decode launches have grid = trajectories x kv heads x 256 threads)."""
+    acc = defaultdict(lambda: [0, 0.0])
+    with open(path, newline="") as f:
+        for r in csv.DictReader(f):
+            if not r["Kernel_Name"].startswith("attention_mfma_kernel"):
+                continue
+            g = int(r.get("Grid_Size_X") or r.get("Grid_Size"))
+            a = acc[g]
+            a[0] += 1
+            a[1] += float(r["End_Timestamp"]) - float(r["Start_Timestamp"])
+    print("| attention_mfma_kernel grid (threads) | launches | avg us |\n|---|---|---|")
+    for g, (n, t) in sorted(acc.items(), key=lambda kv: -kv[1][0])[:6]:
+        print(f"| {g} | {n} | {t / n / 1e3:.2f} |")
+
+
+def main():
+    if sys.argv[1] == "--trace":
+        return trace_summary(sys.argv[2])
+    fetch = read_counter(sys.argv[1], "FETCH_SIZE")
+    write = read_counter(sys.argv[2], "WRITE_SIZE")
+    vocab, hidden, n_traj, n_kv = 151936, 2560, 128, 8
+    copy_bytes = vocab * hidden * 2
+
+    def calib(tab):
+        best = max((max(v) for g in tab.get("__amd_rocclr_copyBuffer", {}).values() for v in [g]), default=None)
+        return copy_bytes / (best * 1024.0) if best else float("nan")
+
+    kf, kw = calib(fetch), calib(write)
+    grid = n_traj * n_kv * 256                      # decode launches: one workgroup per (trajectory, kv head)
+    fa = fetch["attention_mfma_kernel"][grid]
+    wa = write["attention_mfma_kernel"][grid]
+    f_bytes = sum(fa) / len(fa) * 1024.0 * kf
+    w_bytes = sum(wa) / len(wa) * 1024.0 * kw
+    print("# HBM traffic of attention_mfma_kernel, cfg3 rollout (Qwen3-4B shape, 128 trajectories)\n")
+    print("Commands (MI355X box, repository root; one counter per run):\n")
+    print("    rocprofv3 --pmc FETCH_SIZE --kernel-include-regex 'attention_mfma_kernel|copyBuffer' "
+          "--output-format csv -d gpurun_out/pmc_fetch -o f -- python3 bench.py --warmup 0 --no-cpu-baseline")
+    print("    rocprofv3 --pmc WRITE_SIZE --kernel-include-regex 'attention_mfma_kernel|copyBuffer' "
+          "--output-format csv -d gpurun_out/pmc_write -o w -- python3 bench.py --warmup 0 --no-cpu-baseline")
+    print("    python bench_counters.py <f_counter_collection.csv> <w_counter_collection.csv>\n")
+    print(f"Calibration copy: embedding table, {copy_bytes} bytes read and written by `__amd_rocclr_copyBuffer`; "
+          f"FETCH_SIZE factor {kf:.4f}, WRITE_SIZE factor {kw:.4f} (expected bytes / counter KiB x 1024).\n")
+    print(f"Decode launches (grid {grid} threads): {len(fa)} with FETCH_SIZE, {len(wa)} with WRITE_SIZE.\n")
+    print(f"- fetched from HBM per launch: {f_bytes / 1e6:.1f} MB")
+    print(f"- written to HBM per launch: {w_bytes / 1e6:.1f} MB")
+    print(f"- traffic_bytes_per_launch: {f_bytes + w_bytes:.0f}")
+    print(f"- kernel_source_sha256_16: {kernel_source_hash()}")
+
+
+if __name__ == "__main__":
+    main()
