@@ -3,6 +3,7 @@
 // rollout loop (Section 2.3.2).  Host code only; kernels live in kernels_*.hip.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -180,15 +181,22 @@ void forward_generic(rl_model* m, int M, const RowMeta& r) {
 // Split-K factor of a weight-streaming GEMM (tile 128 x 128, 4 waves).  Measured on MI355X: one CU
 // sustains only ~20 GB/s of HBM reads, so a decode GEMM wants a workgroup on every CU: aim for
 // ~240 workgroups, at least four 64-k chunks per split, at most kMaxSplits partial sums (each
-// costs M x N floats of traffic).  Prefill-sized GEMMs already have many row tiles.
+// costs M x N floats of traffic; 8 measured best in the full decode step).  Prefill-sized GEMMs already have many row tiles.
 struct GemmPlan { int nw, splits; };
-const int kMaxSplits = 12;
+const int kMaxSplits = 8;
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return v && *v ? atoi(v) : dflt;
+}
 GemmPlan plan_gemm(int M, int N, int K, bool can_split) {
+  // tuning overrides (development): RL_GEMM_TARGET_WGS, RL_GEMM_MAX_SPLITS
+  static const int target = env_int("RL_GEMM_TARGET_WGS", 240);
+  static const int max_splits = std::min(kMaxSplits, env_int("RL_GEMM_MAX_SPLITS", kMaxSplits));
   int tiles = ((N + 127) / 128) * ((M + 127) / 128);
   int s = 1;
-  if (can_split && M <= 256 && tiles < 240) {
-    s = (240 + tiles / 2) / tiles;
-    s = std::min({s, kMaxSplits, std::max(1, K / 256)});
+  if (can_split && M <= 256 && tiles < target) {
+    s = (target + tiles / 2) / tiles;
+    s = std::min({s, max_splits, std::max(1, K / 256)});
   }
   return GemmPlan{4, std::max(1, s)};
 }

@@ -243,79 +243,94 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   const int pg0 = it.pg_lo + wave * per, pg1 = min(pg0 + per, it.pg_hi);
   const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
 
-  uint4 qreg[4];
+  u32x4 qreg[4];
 #pragma unroll
   for (int c = 0; c < 4; c++) {
-    qreg[c] = make_uint4(0, 0, 0, 0);
+    qreg[c] = (u32x4){0u, 0u, 0u, 0u};
     if (colvalid)
-      qreg[c] = *(const uint4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
+      qreg[c] = *(const u32x4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
   }
   f32x4 acc[8];
 #pragma unroll
   for (int j = 0; j < 8; j++) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
   float m = ATT_NEG, l = 0.f;
 
-  uint4 kc[4], vc[4], kn[4], vn[4];
+  // Two page buffers (A, B) alternate: while one page is consumed the next one is already on its
+  // way, and the page-table entry after that has been requested.  Loads past the end of this
+  // wave's range are clamped to its last page (a re-read that hits in cache) so that nothing in
+  // the loop defines registers conditionally; sched_barrier keeps the loads where they are
+  // written, ahead of the arithmetic.
+  const int pglast = max(pg1 - 1, pg0);
+  const size_t head_off = (size_t)kvh * 2048 + lane * 8;
+  u32x4 kA[4], vA[4], kB[4], vB[4];
+#define ATT_LOAD(KR, VR, PAGEID)                                              \
+  {                                                                           \
+    const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
+    _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
+      KR[c] = *(const u32x4*)(kpool + base_ + c * 512);                       \
+      VR[c] = *(const u32x4*)(vpool + base_ + c * 512);                       \
+    }                                                                         \
+  }
+#define ATT_PAGE(KR, VR, PG)                                                  \
+  {                                                                           \
+    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};                                    \
+    _Pragma("unroll") for (int c = 0; c < 4; c++)                             \
+      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KR[c]), \
+                                                  __builtin_bit_cast(bf16x8, qreg[c]), S, 0, 0, 0); \
+    float sv[4], mx = ATT_NEG;                                                \
+    bool vis[4];                                                              \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                           \
+      int tg = (PG) * RL_PAGE + 4 * g + i;                                    \
+      vis[i] = colvalid && tg <= mypos && (PG) < pg1;                         \
+      sv[i] = vis[i] ? S[i] * scale2 : ATT_NEG;                               \
+      mx = fmaxf(mx, sv[i]);                                                  \
+    }                                                                         \
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                   \
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                   \
+    float mn = fmaxf(m, mx);                                                  \
+    float alpha = exp2f(m - mn);                                              \
+    float ps = 0.f;                                                           \
+    s16x4 pb;                                                                 \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                           \
+      float p = vis[i] ? exp2f(sv[i] - mn) : 0.f;                             \
+      ps += p;                                                                \
+      pb[i] = (short)f2bf(p);                                                 \
+    }                                                                         \
+    l = l * alpha + ps;                                                       \
+    m = mn;                                                                   \
+    _Pragma("unroll") for (int jp = 0; jp < 4; jp++) {                        \
+      s16x4 v0, v1;                                                           \
+      v0[0] = (short)(VR[jp][0] & 0xffff); v0[1] = (short)(VR[jp][0] >> 16);  \
+      v0[2] = (short)(VR[jp][1] & 0xffff); v0[3] = (short)(VR[jp][1] >> 16);  \
+      v1[0] = (short)(VR[jp][2] & 0xffff); v1[1] = (short)(VR[jp][2] >> 16);  \
+      v1[2] = (short)(VR[jp][3] & 0xffff); v1[3] = (short)(VR[jp][3] >> 16);  \
+      _Pragma("unroll") for (int i = 0; i < 4; i++) { acc[2 * jp][i] *= alpha; acc[2 * jp + 1][i] *= alpha; } \
+      acc[2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pb, acc[2 * jp], 0, 0, 0); \
+      acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0); \
+    }                                                                         \
+  }
   if (pg0 < pg1) {
-    size_t base = ((size_t)pt[pg0] * nkv + kvh) * 2048;
-#pragma unroll
-    for (int c = 0; c < 4; c++) {
-      kn[c] = *(const uint4*)(kpool + base + c * 512 + lane * 8);
-      vn[c] = *(const uint4*)(vpool + base + c * 512 + lane * 8);
+    int id_cur = pt[pg0];
+    int id_nxt = pt[min(pg0 + 1, pglast)];
+    ATT_LOAD(kA, vA, id_cur)
+    for (int pg = pg0; pg < pg1; pg += 2) {
+      // page pg is in A; request the table entry of pg+2 (first: the counter of outstanding
+      // loads is in order, and its consumer must not wait for the page behind it), then pg+1 -> B
+      int id_n2 = pt[min(pg + 2, pglast)];
+      ATT_LOAD(kB, vB, id_nxt)
+      __builtin_amdgcn_sched_barrier(0);
+      ATT_PAGE(kA, vA, pg)
+      __builtin_amdgcn_sched_barrier(0);
+      // page pg+1 is in B; request the table entry of pg+3, then pg+2 -> A
+      id_nxt = pt[min(pg + 3, pglast)];
+      ATT_LOAD(kA, vA, id_n2)
+      __builtin_amdgcn_sched_barrier(0);
+      ATT_PAGE(kB, vB, pg + 1)
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
-  for (int pg = pg0; pg < pg1; pg++) {
-#pragma unroll
-    for (int c = 0; c < 4; c++) { kc[c] = kn[c]; vc[c] = vn[c]; }
-    if (pg + 1 < pg1) {
-      size_t base = ((size_t)pt[pg + 1] * nkv + kvh) * 2048;
-#pragma unroll
-      for (int c = 0; c < 4; c++) {
-        kn[c] = *(const uint4*)(kpool + base + c * 512 + lane * 8);
-        vn[c] = *(const uint4*)(vpool + base + c * 512 + lane * 8);
-      }
-    }
-    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int c = 0; c < 4; c++)
-      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[c]),
-                                                  __builtin_bit_cast(bf16x8, qreg[c]), S, 0, 0, 0);
-    float sv[4], mx = ATT_NEG;
-    bool vis[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      int tg = pg * RL_PAGE + 4 * g + i;
-      vis[i] = colvalid && tg <= mypos;
-      sv[i] = vis[i] ? S[i] * scale2 : ATT_NEG;
-      mx = fmaxf(mx, sv[i]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float mn = fmaxf(m, mx);
-    float alpha = exp2f(m - mn);
-    float ps = 0.f;
-    s16x4 pb;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      float p = vis[i] ? exp2f(sv[i] - mn) : 0.f;
-      ps += p;
-      pb[i] = (short)f2bf(p);
-    }
-    l = l * alpha + ps;
-    m = mn;
-#pragma unroll
-    for (int jp = 0; jp < 4; jp++) {
-      s16x4 v0, v1;
-      v0[0] = (short)(vc[jp].x & 0xffff); v0[1] = (short)(vc[jp].x >> 16);
-      v0[2] = (short)(vc[jp].y & 0xffff); v0[3] = (short)(vc[jp].y >> 16);
-      v1[0] = (short)(vc[jp].z & 0xffff); v1[1] = (short)(vc[jp].z >> 16);
-      v1[2] = (short)(vc[jp].w & 0xffff); v1[3] = (short)(vc[jp].w >> 16);
-#pragma unroll
-      for (int i = 0; i < 4; i++) { acc[2 * jp][i] *= alpha; acc[2 * jp + 1][i] *= alpha; }
-      acc[2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pb, acc[2 * jp], 0, 0, 0);
-      acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0);
-    }
-  }
+#undef ATT_LOAD
+#undef ATT_PAGE
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
   // wave partials -> LDS: acc[jb][i] is O^T[d = 16 jb + 4 g + i][column n]
