@@ -250,3 +250,45 @@ def test_full_size_cfg3_launch_configuration_sampled_trajectory():
     # group 1's trajectories took their pages in call order: 5 shared prompt pages, then own pages
     assert list(pg[:4]) == list(g.traj_read(8)[3][:4])
     g.close()
+
+
+def test_bf16_path_is_bit_reproducible_and_empty_calls_are_noops():
+    # split-K partial sums and context parts are combined in a fixed order: two engines fed the same
+    # calls return bit-identical ids, log-probs and logits
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=8, weight_std=0.03, gain_std=0.1)
+    rng = np.random.default_rng(3)
+    toks = rng.integers(0, shape.vocab, 300 + 77)
+    runs = []
+    for _ in range(2):
+        g = rl.RolloutEngine(blob, max_context=512, max_trajectories=4, kv_pool_pages=80)
+        g.append_observation([], [], [])
+        g.append_observation([5, 6], toks, [300, 77])
+        out = [g.decode_step([5, 6], 1.0, 11) for _ in range(5)]
+        ids0, lps0 = g.decode_step([], 1.0, 11)
+        assert len(ids0) == 0 and len(lps0) == 0
+        g.release([])
+        runs.append((np.concatenate([o[0] for o in out]), np.concatenate([o[1] for o in out]),
+                     g.debug_logits(5), g.recompute_logprobs([6, 5], 1.0)))
+        g.close()
+    for a, b in zip(*runs):
+        assert np.array_equal(a, b)
+
+
+def test_recompute_over_several_lm_head_passes():
+    # more rows than one lm-head pass holds: the recompute walks the rows in blocks
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=9, weight_std=0.03, gain_std=0.1)
+    o, g = _pair(shape, blob, max_context=512, max_trajectories=4, kv_pool_pages=80)
+    rng = np.random.default_rng(4)
+    lens = [230, 190]
+    toks = rng.integers(0, shape.vocab, sum(lens))
+    for e in (o, g):
+        e.append_observation([0, 1], toks, lens)
+    for _ in range(3):
+        ids, _ = o.decode_step([0, 1], 1.0, 2)
+        g.decode_step_forced([0, 1], 1.0, ids)
+    ref, rec = o.recompute_logprobs([0, 1], 1.0), g.recompute_logprobs([0, 1], 1.0)
+    assert rec.shape == ref.shape == (sum(lens) + 6,)
+    assert np.abs(rec - ref).max() < TOL_BF16
+    assert np.count_nonzero(rec) == 6 and np.count_nonzero(ref) == 6
