@@ -150,6 +150,7 @@ struct RowMeta {
   int n_items;
   const AttnMerge* merges;
   int n_merges;
+  bool prefill;      // multi-row items (append / recompute) instead of single decode rows
   double kv_bytes;   // keys + values the attention of one layer has to read
   bool time_attn;
 };
@@ -220,7 +221,7 @@ void forward_mfma(rl_model* m, int M, const RowMeta& r) {
                                                 m->page_table, (bf16_t*)m->qb, m->pools[l], md, M);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
     launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, r.merges, r.n_merges,
-                          m->page_table, (bf16_t*)m->xo, m->attn_scratch, md);
+                          m->page_table, (bf16_t*)m->xo, m->attn_scratch, md, r.prefill);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
     GemmPlan po = plan_gemm(M, H, qw, true);
     int so = launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->ph, M, H, qw, EPI_STORE,
@@ -413,7 +414,7 @@ int prefill(rl_model* m, const std::vector<std::pair<Traj*, int>>& work) {
     DevMeta dm;
     int rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, true, 0.0, false};
     forward_rows(m, M, r);
     HIPCHECK(hipGetLastError());
     HIPCHECK(hipStreamSynchronize(m->stream));
@@ -491,7 +492,7 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
       }
     }
   }
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), kvb, timed};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), false, kvb, timed};
   forward_rows(m, n, r);
   lm_head_rows(m, n, 0, n, false);
   bool greedy = temperature == 0.0f;
@@ -560,7 +561,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   int max_pages = (rt->max_context + RL_PAGE - 1) / RL_PAGE;
   m->md = ModelDims{c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads, c.head_dim, c.intermediate,
                     c.vocab, c.rms_eps, c.qk_norm, max_pages};
-  m->rows_per_item = m->mfma ? 16 / (c.n_q_heads / c.n_kv_heads) : 1;
+  m->rows_per_item = m->mfma ? 4 * (16 / (c.n_q_heads / c.n_kv_heads)) : 1;   // prefill items: 4 waves x 16/G rows
   int rc = RL_OK;
 #define TRY(x) do { rc = (x); if (rc) { rl_model_free(m); return rc; } } while (0)
 #define HIPTRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fail(RL_E_HIP, std::string(#x) + ": " + hipGetErrorString(e_)); rl_model_free(m); return RL_E_HIP; } } while (0)
@@ -869,7 +870,7 @@ extern "C" int rl_debug_logits(rl_model* m, int32_t id, float* logits_out) {
   DevMeta dm;
   int rc = upload_meta(m, st, &dm);
   if (rc) return rc;
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), 0.0, false};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), false, 0.0, false};
   forward_rows(m, 1, r);   // rewrites the key / value of position nt-1 with the same values
   lm_head_rows(m, 1, 0, 1, false);
   HIPCHECK(hipGetLastError());
@@ -928,7 +929,7 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
     DevMeta dm;
     rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, true, 0.0, false};
     forward_rows(m, M, r);
     for (int r0 = 0; r0 < M; r0 += m->Rl) {
       int R = std::min(m->Rl, M - r0);

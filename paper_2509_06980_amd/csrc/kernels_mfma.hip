@@ -199,6 +199,77 @@ int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, 
 // =============================================================================================
 #define ATT_NEG (-1.0e30f)
 
+// One page of the online-softmax loop; see the kernels below for the variables they use.
+#define ATT_LOAD(KR, VR, PAGEID)                                              \
+  {                                                                           \
+    const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
+    _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
+      KR[c] = *(const u32x4*)(kpool + base_ + c * 512);                       \
+      VR[c] = *(const u32x4*)(vpool + base_ + c * 512);                       \
+    }                                                                         \
+  }
+#define ATT_PAGE(KR, VR, PG)                                                  \
+  {                                                                           \
+    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};                                    \
+    _Pragma("unroll") for (int c = 0; c < 4; c++)                             \
+      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KR[c]), \
+                                                  __builtin_bit_cast(bf16x8, qreg[c]), S, 0, 0, 0); \
+    float sv[4], mx = ATT_NEG;                                                \
+    bool vis[4];                                                              \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                           \
+      int tg = (PG) * RL_PAGE + 4 * g + i;                                    \
+      vis[i] = colvalid && tg <= mypos && (PG) < pg1;                         \
+      sv[i] = vis[i] ? S[i] * scale2 : ATT_NEG;                               \
+      mx = fmaxf(mx, sv[i]);                                                  \
+    }                                                                         \
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                   \
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                   \
+    float mn = fmaxf(m, mx);                                                  \
+    float alpha = exp2f(m - mn);                                              \
+    float ps = 0.f;                                                           \
+    s16x4 pb;                                                                 \
+    _Pragma("unroll") for (int i = 0; i < 4; i++) {                           \
+      float p = vis[i] ? exp2f(sv[i] - mn) : 0.f;                             \
+      ps += p;                                                                \
+      pb[i] = (short)f2bf(p);                                                 \
+    }                                                                         \
+    l = l * alpha + ps;                                                       \
+    m = mn;                                                                   \
+    _Pragma("unroll") for (int jp = 0; jp < 4; jp++) {                        \
+      s16x4 v0, v1;                                                           \
+      v0[0] = (short)(VR[jp][0] & 0xffff); v0[1] = (short)(VR[jp][0] >> 16);  \
+      v0[2] = (short)(VR[jp][1] & 0xffff); v0[3] = (short)(VR[jp][1] >> 16);  \
+      v1[0] = (short)(VR[jp][2] & 0xffff); v1[1] = (short)(VR[jp][2] >> 16);  \
+      v1[2] = (short)(VR[jp][3] & 0xffff); v1[3] = (short)(VR[jp][3] >> 16);  \
+      _Pragma("unroll") for (int i = 0; i < 4; i++) { acc[2 * jp][i] *= alpha; acc[2 * jp + 1][i] *= alpha; } \
+      acc[2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pb, acc[2 * jp], 0, 0, 0); \
+      acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0); \
+    }                                                                         \
+  }
+// The page loop shared by the decode and the prefill kernel (uses pt, pg0, pg1, pglast, head_off,
+// kpool, vpool, nkv and the buffers kA, vA, kB, vB of the enclosing kernel).
+#define ATT_PAGE_LOOP                                                         \
+  if (pg0 < pg1) {                                                            \
+    int id_cur = pt[pg0];                                                     \
+    int id_nxt = pt[min(pg0 + 1, pglast)];                                    \
+    ATT_LOAD(kA, vA, id_cur)                                                  \
+    for (int pg = pg0; pg < pg1; pg += 2) {                                   \
+      /* page pg is in A; request the table entry of pg+2 (first: the counter of outstanding \
+         loads is in order, and its consumer must not wait for the page behind it), then pg+1 -> B */ \
+      int id_n2 = pt[min(pg + 2, pglast)];                                    \
+      ATT_LOAD(kB, vB, id_nxt)                                                \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      ATT_PAGE(kA, vA, pg)                                                    \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      /* page pg+1 is in B; request the table entry of pg+3, then pg+2 -> A */ \
+      id_nxt = pt[min(pg + 3, pglast)];                                       \
+      ATT_LOAD(kA, vA, id_n2)                                                 \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      ATT_PAGE(kB, vB, pg + 1)                                                \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+    }                                                                         \
+  }
+
 __device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
                                                  const float* __restrict__ pl,
                                                  const float* __restrict__ pacc, int nparts,
@@ -263,74 +334,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   const int pglast = max(pg1 - 1, pg0);
   const size_t head_off = (size_t)kvh * 2048 + lane * 8;
   u32x4 kA[4], vA[4], kB[4], vB[4];
-#define ATT_LOAD(KR, VR, PAGEID)                                              \
-  {                                                                           \
-    const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
-    _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
-      KR[c] = *(const u32x4*)(kpool + base_ + c * 512);                       \
-      VR[c] = *(const u32x4*)(vpool + base_ + c * 512);                       \
-    }                                                                         \
-  }
-#define ATT_PAGE(KR, VR, PG)                                                  \
-  {                                                                           \
-    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};                                    \
-    _Pragma("unroll") for (int c = 0; c < 4; c++)                             \
-      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KR[c]), \
-                                                  __builtin_bit_cast(bf16x8, qreg[c]), S, 0, 0, 0); \
-    float sv[4], mx = ATT_NEG;                                                \
-    bool vis[4];                                                              \
-    _Pragma("unroll") for (int i = 0; i < 4; i++) {                           \
-      int tg = (PG) * RL_PAGE + 4 * g + i;                                    \
-      vis[i] = colvalid && tg <= mypos && (PG) < pg1;                         \
-      sv[i] = vis[i] ? S[i] * scale2 : ATT_NEG;                               \
-      mx = fmaxf(mx, sv[i]);                                                  \
-    }                                                                         \
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                   \
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                   \
-    float mn = fmaxf(m, mx);                                                  \
-    float alpha = exp2f(m - mn);                                              \
-    float ps = 0.f;                                                           \
-    s16x4 pb;                                                                 \
-    _Pragma("unroll") for (int i = 0; i < 4; i++) {                           \
-      float p = vis[i] ? exp2f(sv[i] - mn) : 0.f;                             \
-      ps += p;                                                                \
-      pb[i] = (short)f2bf(p);                                                 \
-    }                                                                         \
-    l = l * alpha + ps;                                                       \
-    m = mn;                                                                   \
-    _Pragma("unroll") for (int jp = 0; jp < 4; jp++) {                        \
-      s16x4 v0, v1;                                                           \
-      v0[0] = (short)(VR[jp][0] & 0xffff); v0[1] = (short)(VR[jp][0] >> 16);  \
-      v0[2] = (short)(VR[jp][1] & 0xffff); v0[3] = (short)(VR[jp][1] >> 16);  \
-      v1[0] = (short)(VR[jp][2] & 0xffff); v1[1] = (short)(VR[jp][2] >> 16);  \
-      v1[2] = (short)(VR[jp][3] & 0xffff); v1[3] = (short)(VR[jp][3] >> 16);  \
-      _Pragma("unroll") for (int i = 0; i < 4; i++) { acc[2 * jp][i] *= alpha; acc[2 * jp + 1][i] *= alpha; } \
-      acc[2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pb, acc[2 * jp], 0, 0, 0); \
-      acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0); \
-    }                                                                         \
-  }
-  if (pg0 < pg1) {
-    int id_cur = pt[pg0];
-    int id_nxt = pt[min(pg0 + 1, pglast)];
-    ATT_LOAD(kA, vA, id_cur)
-    for (int pg = pg0; pg < pg1; pg += 2) {
-      // page pg is in A; request the table entry of pg+2 (first: the counter of outstanding
-      // loads is in order, and its consumer must not wait for the page behind it), then pg+1 -> B
-      int id_n2 = pt[min(pg + 2, pglast)];
-      ATT_LOAD(kB, vB, id_nxt)
-      __builtin_amdgcn_sched_barrier(0);
-      ATT_PAGE(kA, vA, pg)
-      __builtin_amdgcn_sched_barrier(0);
-      // page pg+1 is in B; request the table entry of pg+3, then pg+2 -> A
-      id_nxt = pt[min(pg + 3, pglast)];
-      ATT_LOAD(kA, vA, id_n2)
-      __builtin_amdgcn_sched_barrier(0);
-      ATT_PAGE(kB, vB, pg + 1)
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-#undef ATT_LOAD
-#undef ATT_PAGE
+  ATT_PAGE_LOOP
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
   // wave partials -> LDS: acc[jb][i] is O^T[d = 16 jb + 4 g + i][column n]
@@ -363,6 +367,59 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   }
 }
 
+// Chunked prefill: one workgroup per (item of up to 4 * 16/G rows, kv head).  Wave w owns the
+// item's rows [w * 16/G, (w+1) * 16/G) with all G heads of the group as its 16 MFMA columns and
+// walks every page those rows may see; the four waves read the same pages at about the same time,
+// so keys / values come from HBM once per 4 * 16/G query rows.  No cross-wave merge is needed.
+__global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kpool, const bf16_t* __restrict__ vpool,
+    const AttnItem* __restrict__ items, const int32_t* __restrict__ page_table,
+    bf16_t* __restrict__ o, int nq, int nkv, int gshift, int pt_stride, float scale2) {
+  const int item_idx = blockIdx.x / nkv;
+  const AttnItem it = items[item_idx];
+  const int kvh = blockIdx.x - item_idx * nkv;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane >> 4, n = lane & 15, hq = n & ((1 << gshift) - 1);
+  const int rpw = 16 >> gshift;                       // rows per wave
+  const int r = wave * rpw + (n >> gshift);           // row within the item
+  const bool colvalid = r < it.nrows;
+  const int mypos = it.pos0 + r;
+  const int wave_rows = min(it.nrows - wave * rpw, rpw);
+  const int pg0 = 0;
+  const int pg1 = wave_rows > 0 ? (it.pos0 + wave * rpw + wave_rows - 1) / RL_PAGE + 1 : 0;
+  const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
+  u32x4 qreg[4];
+#pragma unroll
+  for (int c = 0; c < 4; c++) {
+    qreg[c] = (u32x4){0u, 0u, 0u, 0u};
+    if (colvalid)
+      qreg[c] = *(const u32x4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
+  }
+  f32x4 acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; j++) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m = ATT_NEG, l = 0.f;
+  const int pglast = max(pg1 - 1, pg0);
+  const size_t head_off = (size_t)kvh * 2048 + lane * 8;
+  u32x4 kA[4], vA[4], kB[4], vB[4];
+  ATT_PAGE_LOOP
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (colvalid) {
+    // acc[jb][i] is O[row r][head hq][d = 16 jb + 4 g + i]: four consecutive dims = one 8-byte store
+    const float inv = 1.0f / l;
+    const size_t base = atile_off(it.row0 + r, ((kvh << gshift) + hq) * 128 + 4 * g, nq * 128);
+#pragma unroll
+    for (int jb = 0; jb < 8; jb++) {
+      uint2 w;
+      w.x = (uint32_t)f2bf(acc[jb][0] * inv) | ((uint32_t)f2bf(acc[jb][1] * inv) << 16);
+      w.y = (uint32_t)f2bf(acc[jb][2] * inv) | ((uint32_t)f2bf(acc[jb][3] * inv) << 16);
+      // k advances by 16 per jb: two A-tile k-blocks of 16 per 32 dims => +1 k-block each step
+      *(uint2*)(o + base + (size_t)jb * (4 * 64 * 8)) = w;
+    }
+  }
+}
+
 // grid (n_merges, nkv), block 256: merge the parts of one (row, kv head) in ascending order
 __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ scratch,
                                                               const AttnMerge* __restrict__ merges,
@@ -391,11 +448,17 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __res
 void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
                            int n_items, const AttnMerge* merges, int n_merges,
                            const int32_t* page_table, bf16_t* o, float* scratch,
-                           const ModelDims& md) {
+                           const ModelDims& md, bool prefill) {
   if (n_items <= 0) return;
   float scale2 = 1.4426950408889634f / sqrtf((float)md.d);
   int gshift = 0;
   while ((1 << gshift) < md.nq / md.nkv) gshift++;
+  if (prefill) {
+    attention_prefill_mfma_kernel<<<n_items * md.nkv, 256, 0, s>>>(
+        q, (const bf16_t*)pool.k, (const bf16_t*)pool.v, items, page_table, o, md.nq, md.nkv, gshift,
+        md.max_pages_per_traj, scale2);
+    return;
+  }
   attention_mfma_kernel<<<n_items * md.nkv, 256, 0, s>>>(q, (const bf16_t*)pool.k,
                                                         (const bf16_t*)pool.v, items, page_table, o,
                                                         scratch, md.nq, md.nkv, gshift,
