@@ -25,6 +25,9 @@ CONFIGS = {
     "cfg2": ("qwen3-0.6b", "cfg2"),
     "cfg3": ("qwen3-4b", "cfg3"),
     "cfg4": ("qwen3-4b", "cfg4"),
+    # one wave of 128 of cfg5's 256 trajectories (the full KV does not fit one GPU), followed by the
+    # full-trajectory masked log-prob recompute; use --scale < 1 unless ~270 GB of HBM are free
+    "cfg5": ("qwen3-8b", "cfg5-wave"),
 }
 HBM_PEAK_GBS = 8000.0
 
@@ -83,6 +86,21 @@ def run_rollout(engine, w, shape, stats):
             engine.release(ev[1])
             for i in ev[1]:
                 ctx.pop(int(i), None)
+    if ctx:   # workload without a final release (cfg5): recompute all log-probs, then release
+        ids = np.array(sorted(ctx), np.int32)
+        gen = {int(i): engine.traj_read(int(i)) for i in ids[:4]}
+        t0 = time.perf_counter()
+        lp = engine.recompute_logprobs(ids, 1.0)
+        stats["recompute_s"] = stats.get("recompute_s", 0.0) + time.perf_counter() - t0
+        stats["recompute_tokens"] = stats.get("recompute_tokens", 0) + int(lp.size)
+        off, worst = 0, 0.0
+        for i in ids[:4]:      # recomputed values against the log-probs returned at generation time
+            _, mask, glp, _ = gen[int(i)]
+            worst = max(worst, float(np.abs(lp[off:off + glp.size] - glp).max()))
+            assert np.all(lp[off:off + glp.size][mask == 1] == 0.0)
+            off += ctx[int(i)]
+        stats["recompute_max_abs_diff"] = worst
+        engine.release(ids)
     return n_gen
 
 
@@ -196,6 +214,10 @@ def main():
                             "frac": round(stats["decode_bytes"] / stats["decode_s"] / 1e9 / HBM_PEAK_GBS, 4),
                             "note": "algorithmic bytes of all decode steps / wall time inside rl_decode_step"}
         if stats["decode_s"] else None,
+        "recompute": {"tokens_per_s": round(stats["recompute_tokens"] / stats["recompute_s"], 1),
+                      "tokens": stats["recompute_tokens"], "seconds": round(stats["recompute_s"], 3),
+                      "max_abs_diff_vs_generation_logprobs": round(stats["recompute_max_abs_diff"], 5)}
+        if stats.get("recompute_s") else None,
         "append_s_per_step": round(stats["append_s"] / max(args.steps, 1), 3),
         "decode_s_per_step": round(stats["decode_s"] / max(args.steps, 1), 3),
         "roofline": roofline,
