@@ -182,6 +182,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     attn_ms, attn_n, attn_bytes, attn_unique = eng.timing_read(reset=True)
+    step_gpu_ms, steps_timed = eng.timing_read_steps(reset=True)
     eng.timing_enable(0)
 
     roofline = None
@@ -218,6 +219,8 @@ def main():
                       "tokens": stats["recompute_tokens"], "seconds": round(stats["recompute_s"], 3),
                       "max_abs_diff_vs_generation_logprobs": round(stats["recompute_max_abs_diff"], 5)}
         if stats.get("recompute_s") else None,
+        "decode_step_gpu_ms_sampled": round(step_gpu_ms / steps_timed, 3) if steps_timed else None,
+        "decode_step_wall_ms_mean": round(stats["decode_s"] * 1e3 / max(stats["decode_steps"], 1), 3),
         "append_s_per_step": round(stats["append_s"] / max(args.steps, 1), 3),
         "decode_s_per_step": round(stats["decode_s"] / max(args.steps, 1), 3),
         "roofline": roofline,

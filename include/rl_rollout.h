@@ -157,6 +157,8 @@ uint32_t rl_uniform_u32(uint64_t seed, int32_t traj_id, int32_t position);
 int rl_timing_enable(rl_model* m, int32_t every);
 int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches, double* attn_kv_bytes,
                    double* attn_kv_unique_bytes, int reset);
+/* GPU time of the timed decode steps, first kernel to sampler (HIP events), and their count. */
+int rl_timing_read_steps(rl_model* m, double* step_gpu_ms, int64_t* steps, int reset);
 
 #ifdef __cplusplus
 }

@@ -11,7 +11,7 @@ EXPORTED_SYMBOLS = [
     "rl_append_observation", "rl_decode_step", "rl_release", "rl_fork", "rl_traj_info",
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
     "rl_decode_step_forced", "rl_sample_from_logits", "rl_uniform_u32", "rl_timing_enable",
-    "rl_timing_read",
+    "rl_timing_read", "rl_timing_read_steps",
 ]
 
 
@@ -71,6 +71,7 @@ def load_library():
     lib.rl_timing_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.rl_timing_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int]
+    lib.rl_timing_read_steps.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
     _lib = lib
     return lib
 
@@ -205,3 +206,8 @@ class RolloutEngine:
         _check(self._lib.rl_timing_read(self._h, C.byref(ms), C.byref(n), C.byref(b), C.byref(u),
                                         int(reset)))
         return ms.value, n.value, b.value, u.value
+
+    def timing_read_steps(self, reset=True):
+        ms, n = C.c_double(), C.c_int64()
+        _check(self._lib.rl_timing_read_steps(self._h, C.byref(ms), C.byref(n), int(reset)))
+        return ms.value, n.value

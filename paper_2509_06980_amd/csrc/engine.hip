@@ -87,7 +87,9 @@ struct rl_model {
   // timing
   int timing_every = 0;
   int64_t decode_steps = 0, attn_launches = 0;
-  double attn_ms = 0.0, attn_bytes = 0.0, attn_unique_bytes = 0.0;
+  double attn_ms = 0.0, attn_bytes = 0.0, attn_unique_bytes = 0.0, step_gpu_ms = 0.0, step_wall_ms = 0.0;
+  int64_t steps_timed = 0;
+  hipEvent_t ev_step[2] = {nullptr, nullptr};
   std::vector<uint32_t> page_stamp;   // per page: last timed step that counted it
   uint32_t stamp = 0;
   std::vector<hipEvent_t> ev;
@@ -493,6 +495,7 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
     }
   }
   RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), false, kvb, timed};
+  if (timed) (void)hipEventRecord(m->ev_step[0], m->stream);
   forward_rows(m, n, r);
   lm_head_rows(m, n, 0, n, false);
   bool greedy = temperature == 0.0f;
@@ -500,10 +503,16 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
   launch_sampler(m->stream, m->logits, (size_t)m->md.V, n, m->md.V, c, greedy ? 1 : 0, nullptr, seed,
                  dm.traj, dm.newpos, forced ? dm.forced : nullptr, nullptr, m->ss, m->d_ids, m->d_lp);
   HIPCHECK(hipGetLastError());
+  if (timed) (void)hipEventRecord(m->ev_step[1], m->stream);
   HIPCHECK(hipMemcpyAsync(m->h_ids, m->d_ids, n * 4, hipMemcpyDeviceToHost, m->stream));
   HIPCHECK(hipMemcpyAsync(m->h_lp, m->d_lp, n * 4, hipMemcpyDeviceToHost, m->stream));
   HIPCHECK(hipStreamSynchronize(m->stream));
   if (timed) {
+    float sms = 0.f;
+    if (hipEventElapsedTime(&sms, m->ev_step[0], m->ev_step[1]) == hipSuccess) {
+      m->step_gpu_ms += sms;
+      m->steps_timed++;
+    }
     for (int l = 0; l < m->md.L; l++) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, m->ev[2 * l], m->ev[2 * l + 1]) == hipSuccess) {
@@ -679,6 +688,8 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   HIPTRY(hipHostMalloc((void**)&m->h_lp, (size_t)m->Rl * 4));
   m->ev.resize(2 * c.n_layers);
   for (auto& e : m->ev) HIPTRY(hipEventCreate(&e));
+  HIPTRY(hipEventCreate(&m->ev_step[0]));
+  HIPTRY(hipEventCreate(&m->ev_step[1]));
   HIPTRY(hipDeviceSynchronize());
 #undef TRY
 #undef HIPTRY
@@ -694,6 +705,7 @@ extern "C" void rl_model_free(rl_model* m) {
   if (m->h_ids) (void)hipHostFree(m->h_ids);
   if (m->h_lp) (void)hipHostFree(m->h_lp);
   for (auto e : m->ev) if (e) (void)hipEventDestroy(e);
+  for (auto e : m->ev_step) if (e) (void)hipEventDestroy(e);
   if (m->stream) (void)hipStreamDestroy(m->stream);
   delete m;
 }
@@ -986,6 +998,14 @@ extern "C" int rl_sample_from_logits(const float* logits, int32_t rows, int32_t 
 extern "C" int rl_timing_enable(rl_model* m, int32_t every) {
   if (!m || every < 0) return fail(RL_E_ARG, "bad argument");
   m->timing_every = every;
+  return RL_OK;
+}
+
+extern "C" int rl_timing_read_steps(rl_model* m, double* step_gpu_ms, int64_t* steps, int reset) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (step_gpu_ms) *step_gpu_ms = m->step_gpu_ms;
+  if (steps) *steps = m->steps_timed;
+  if (reset) { m->step_gpu_ms = 0.0; m->steps_timed = 0; }
   return RL_OK;
 }
 

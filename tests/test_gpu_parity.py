@@ -292,3 +292,44 @@ def test_recompute_over_several_lm_head_passes():
     assert rec.shape == ref.shape == (sum(lens) + 6,)
     assert np.abs(rec - ref).max() < TOL_BF16
     assert np.count_nonzero(rec) == 6 and np.count_nonzero(ref) == 6
+
+
+def test_full_size_cfg2_shape_sampled_trajectories():
+    """Qwen3-0.6B shape (GQA group 2, 28 layers), 64 trajectories as in cfg2: two trajectories are
+    followed by the oracle, teacher-forcing the GPU with the oracle's ids."""
+    shape = SHAPES["qwen3-0.6b"]
+    blob = make_weight_blob(shape, seed=1)
+    n_traj, prompt, obs = 64, 40, 12
+    checks = [3, 41]
+    g = rl.RolloutEngine(blob, max_context=128, max_trajectories=n_traj, kv_pool_pages=n_traj * 9)
+    o = OracleEngine(blob, max_context=128, max_trajectories=2, kv_pool_pages=32)
+    rng = np.random.default_rng(5)
+    ids = np.arange(n_traj, dtype=np.int32)
+    prompts = rng.integers(0, shape.vocab, (n_traj, prompt), dtype=np.int32)
+    g.append_observation(ids, prompts.reshape(-1), np.full(n_traj, prompt, np.int32))
+    o.append_observation(checks, prompts[checks].reshape(-1), [prompt, prompt])
+    worst = 0.0
+    for turn in range(2):
+        for step in range(3):
+            tok, lp = o.decode_step(checks, 1.0, 3)
+            forced = rng.integers(0, shape.vocab, n_traj, dtype=np.int32)
+            forced[checks] = tok
+            glp = g.decode_step_forced(ids, 1.0, forced)
+            worst = max(worst, float(np.abs(glp[checks] - lp).max()))
+        if turn == 0:
+            chunk = rng.integers(0, shape.vocab, (n_traj, obs), dtype=np.int32)
+            g.append_observation(ids, chunk.reshape(-1), np.full(n_traj, obs, np.int32))
+            o.append_observation(checks, chunk[checks].reshape(-1), [obs, obs])
+    from oracle.bf16_error_model import forward_bf16_model
+    zo, zg = o.debug_logits(checks[0]), g.debug_logits(checks[0])
+    zm = forward_bf16_model(o.model, o.traj_read(checks[0])[0])[-1]
+    rms_model = float(np.sqrt(((zm - zo) ** 2).mean()))
+    rms_gpu = float(np.sqrt(((zg - zo) ** 2).mean()))
+    print("cfg2 shape: max |dlogp|", worst, "rms gpu", rms_gpu, "rms model", rms_model,
+          "max gpu", float(np.abs(zg - zo).max()))
+    assert rms_gpu < 1.5 * rms_model + 1e-3
+    assert np.abs(zg - zo).max() < max(TOL_BF16, 7.0 * rms_model)
+    assert worst < max(TOL_BF16, 4.0 * rms_model)
+    for c in checks:
+        compare_records(o, g, c)
+    g.close()
