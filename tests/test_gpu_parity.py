@@ -330,6 +330,8 @@ def test_full_size_cfg2_shape_sampled_trajectories():
     assert rms_gpu < 1.5 * rms_model + 1e-3
     assert np.abs(zg - zo).max() < max(TOL_BF16, 7.0 * rms_model)
     assert worst < max(TOL_BF16, 4.0 * rms_model)
-    for c in checks:
-        compare_records(o, g, c)
+    for c in checks:      # (page indices differ: the oracle holds only the two checked trajectories)
+        to, mo = o.traj_read(c)[:2]
+        tg, mg = g.traj_read(c)[:2]
+        assert np.array_equal(to, tg) and np.array_equal(mo, mg)
     g.close()
