@@ -4,7 +4,8 @@
 One step = one full pass of the rollout hot path over one synthetic workload: prompt prefill
 (+ group fork), then per turn the decode steps and the observation append, then release.
 The default workload is the Qwen3-4B-shaped, 128-trajectory, 4-turn configuration ("cfg3").
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: the throughput, the roofline of the dominant kernel (decode attention) and a
+CPU baseline (the oracle on a small slice).
 """
 import argparse
 import json
@@ -141,8 +142,9 @@ def main():
     ap.add_argument("--timing-every", type=int, default=16)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (trajectories are independent; "
-              "see DESIGN.md for how the path would shard). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU: trajectories are independent, so more GPUs "
+              "would each take whole groups of trajectories with replicated weights and no exchange "
+              "during the rollout; that path is not built. Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -73,9 +73,9 @@ def main():
     print("# HBM traffic of attention_mfma_kernel, cfg3 rollout (Qwen3-4B shape, 128 trajectories)\n")
     print("Commands (MI355X box, repository root; one counter per run):\n")
     print("    rocprofv3 --pmc FETCH_SIZE --kernel-include-regex 'attention_mfma_kernel|copyBuffer' "
-          "--output-format csv -d gpurun_out/pmc_fetch -o f -- python3 bench.py --warmup 0 --no-cpu-baseline")
+          "--output-format csv -d out/pmc_fetch -o f -- python3 bench.py --warmup 0 --no-cpu-baseline")
     print("    rocprofv3 --pmc WRITE_SIZE --kernel-include-regex 'attention_mfma_kernel|copyBuffer' "
-          "--output-format csv -d gpurun_out/pmc_write -o w -- python3 bench.py --warmup 0 --no-cpu-baseline")
+          "--output-format csv -d out/pmc_write -o w -- python3 bench.py --warmup 0 --no-cpu-baseline")
     print("    python bench_counters.py <f_counter_collection.csv> <w_counter_collection.csv>\n")
     print(f"Calibration copy: embedding table, {copy_bytes} bytes read and written by `__amd_rocclr_copyBuffer`; "
           f"FETCH_SIZE factor {kf:.4f}, WRITE_SIZE factor {kw:.4f} (expected bytes / counter KiB x 1024).\n")
