@@ -31,6 +31,7 @@ CONFIGS = {
     "cfg5": ("qwen3-8b", "cfg5-wave"),
 }
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def recorded_traffic(config):
@@ -58,10 +59,17 @@ def run_rollout(engine, w, shape, stats):
     n_gen = 0
     for ev in w.events:
         kind = ev[0]
+        if kind != "decode" and stats.get("turns"):
+            stats["turns"][-1]["closed"] = True
         if kind == "append":
             t0 = time.perf_counter()
             engine.append_observation(ev[1], ev[2], ev[3])
             stats["append_s"] += time.perf_counter() - t0
+            stats["append_rows"] = stats.get("append_rows", 0) + int(np.sum(ev[3]))
+            # causal attention of the appended rows: row at position p attends to p + 1 keys
+            for i, c in zip(ev[1], ev[3]):
+                c0 = ctx.get(int(i), 0)
+                stats["append_attn_keys"] = stats.get("append_attn_keys", 0) + c0 * int(c) + int(c) * (int(c) + 1) // 2
             for i, c in zip(ev[1], ev[3]):
                 ctx[int(i)] = ctx.get(int(i), 0) + int(c)
         elif kind == "fork":
@@ -73,16 +81,29 @@ def run_rollout(engine, w, shape, stats):
         elif kind == "decode":
             t0 = time.perf_counter()
             engine.decode_step(ev[1], ev[2], ev[3])
-            stats["decode_s"] += time.perf_counter() - t0
+            dt = time.perf_counter() - t0
+            stats["decode_s"] += dt
             tot = 0
             for i in ev[1]:
                 tot += ctx[int(i)]
                 ctx[int(i)] += 1
             # algorithmic bytes of this decode step: weights once, every cached key/value once,
             # one new key/value row per trajectory
-            stats["decode_bytes"] += wbytes + (tot + len(ev[1])) * kvtok
+            nbytes = wbytes + (tot + len(ev[1])) * kvtok
+            stats["decode_bytes"] += nbytes
             stats["decode_steps"] += 1
             n_gen += len(ev[1])
+            # the same figures per run of consecutive decode steps (one generation turn)
+            turns = stats.setdefault("turns", [])
+            if not turns or turns[-1]["closed"]:
+                turns.append(dict(closed=False, steps=0, s=0.0, bytes=0.0, tokens=0,
+                                  ctx_first=tot / len(ev[1]), ctx_last=0.0))
+            tr = turns[-1]
+            tr["steps"] += 1
+            tr["s"] += dt
+            tr["bytes"] += nbytes
+            tr["tokens"] += len(ev[1])
+            tr["ctx_last"] = tot / len(ev[1])
         elif kind == "release":
             engine.release(ev[1])
             for i in ev[1]:
@@ -103,6 +124,20 @@ def run_rollout(engine, w, shape, stats):
         stats["recompute_max_abs_diff"] = worst
         engine.release(ids)
     return n_gen
+
+
+def append_mfma(stats, shape):
+    """Dense-contraction rate of the chunked prefill (appends + forks, wall time): linear layers of
+    every appended row plus causal attention (QK^T and PV) over the keys each row sees."""
+    rows = stats.get("append_rows", 0)
+    if not rows or not stats["append_s"]:
+        return None
+    flops = 2.0 * shape.linear_params() * rows \
+        + 4.0 * shape.n_q_heads * shape.head_dim * shape.n_layers * stats.get("append_attn_keys", 0)
+    tf = flops / stats["append_s"] / 1e12
+    return {"achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "rows": int(rows),
+            "note": "algorithmic flops of all appends / wall time inside rl_append_observation and rl_fork"}
 
 
 def cpu_baseline(blob, shape, budget_note):
@@ -223,6 +258,14 @@ def main():
         if stats.get("recompute_s") else None,
         "decode_step_gpu_ms_sampled": round(step_gpu_ms / steps_timed, 3) if steps_timed else None,
         "decode_step_wall_ms_mean": round(stats["decode_s"] * 1e3 / max(stats["decode_steps"], 1), 3),
+        "decode_by_turn": [
+            {"mean_context_first_step": round(t["ctx_first"]), "mean_context_last_step": round(t["ctx_last"]),
+             "decode_steps": t["steps"], "tokens_per_s": round(t["tokens"] / t["s"], 1),
+             "ms_per_decode_step": round(t["s"] * 1e3 / t["steps"], 3),
+             "hbm_GBs": round(t["bytes"] / t["s"] / 1e9, 1),
+             "hbm_frac": round(t["bytes"] / t["s"] / 1e9 / HBM_PEAK_GBS, 4)}
+            for t in stats.get("turns", [])],
+        "append_mfma": append_mfma(stats, shape),
         "append_s_per_step": round(stats["append_s"] / max(args.steps, 1), 3),
         "decode_s_per_step": round(stats["decode_s"] / max(args.steps, 1), 3),
         "roofline": roofline,

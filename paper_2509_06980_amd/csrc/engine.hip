@@ -77,6 +77,7 @@ struct rl_model {
   SamplerScratch ss{};
   int32_t *d_ids = nullptr, *h_ids = nullptr;
   float *d_lp = nullptr, *h_lp = nullptr;
+  float *d_zt = nullptr, *d_lp_rows = nullptr, *h_lp_rows = nullptr;   // masked log-prob pass: Mcap rows
   uint8_t* d_mask = nullptr;
   // host state
   std::unordered_map<int32_t, Traj> traj;
@@ -681,11 +682,14 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc((void**)&m->d_ids, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_lp, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_mask, Mc));
+  TRY(m->dalloc((void**)&m->d_zt, Mc * 4));
+  TRY(m->dalloc((void**)&m->d_lp_rows, Mc * 4));
   m->meta_ints = 32 * Mc + 3 * 65536;
   TRY(m->dalloc((void**)&m->d_meta, m->meta_ints * 4));
   HIPTRY(hipHostMalloc((void**)&m->h_meta, m->meta_ints * 4));
   HIPTRY(hipHostMalloc((void**)&m->h_ids, (size_t)m->Rl * 4));
   HIPTRY(hipHostMalloc((void**)&m->h_lp, (size_t)m->Rl * 4));
+  HIPTRY(hipHostMalloc((void**)&m->h_lp_rows, Mc * 4));
   m->ev.resize(2 * c.n_layers);
   for (auto& e : m->ev) HIPTRY(hipEventCreate(&e));
   HIPTRY(hipEventCreate(&m->ev_step[0]));
@@ -704,6 +708,7 @@ extern "C" void rl_model_free(rl_model* m) {
   if (m->h_meta) (void)hipHostFree(m->h_meta);
   if (m->h_ids) (void)hipHostFree(m->h_ids);
   if (m->h_lp) (void)hipHostFree(m->h_lp);
+  if (m->h_lp_rows) (void)hipHostFree(m->h_lp_rows);
   for (auto e : m->ev) if (e) (void)hipEventDestroy(e);
   for (auto e : m->ev_step) if (e) (void)hipEventDestroy(e);
   if (m->stream) (void)hipStreamDestroy(m->stream);
@@ -938,11 +943,43 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
     if (M == 0) break;
     st.traj.assign(M, 0);
     st.newpos.assign(M, 0);
+    // rows whose target token was sampled by the policy (mask 0): only they need the lm-head.
+    // Their row numbers and targets travel in the two metadata arrays this pass does not use.
+    int nsel = 0;
+    if (m->mfma)
+      for (int k = 0; k < M; k++)
+        if (st.mask[k] == 0) {
+          st.traj[nsel] = k;
+          st.newpos[nsel] = st.forced[k];
+          dest[nsel] = dest[k];
+          nsel++;
+        }
     DevMeta dm;
     rc = upload_meta(m, st, &dm);
     if (rc) return rc;
     RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, true, 0.0, false};
     forward_rows(m, M, r);
+    if (m->mfma) {
+      // fused pass: gather + final norm, lm-head with the log-softmax reduced in its epilogue (the
+      // logits are never stored; the logits buffer serves as scratch for the per-strip statistics)
+      const ModelDims& md = m->md;
+      size_t per_row = (size_t)(md.V / 32) * 8;
+      int rows_cap = (int)std::min<size_t>((size_t)m->Mcap, (size_t)m->Rl * md.V * 4 / per_row);
+      for (int c0 = 0; c0 < nsel; c0 += rows_cap) {
+        int R = std::min(rows_cap, nsel - c0);
+        launch_add_rmsnorm(m->stream, m->h, m->ph, m->pending_parts, (size_t)M * md.H,
+                           (const bf16_t*)m->g_final, (bf16_t*)m->xa, R, md.H, md.eps, dm.traj + c0);
+        launch_lm_head_logprob(m->stream, (const bf16_t*)m->xa, (const bf16_t*)m->lm_head, R, md.V, md.H,
+                               dm.newpos + c0, c, m->logits, m->d_zt, m->d_lp_rows + c0);
+      }
+      m->pending_parts = 0;
+      HIPCHECK(hipGetLastError());
+      if (nsel > 0)
+        HIPCHECK(hipMemcpyAsync(m->h_lp_rows, m->d_lp_rows, (size_t)nsel * 4, hipMemcpyDeviceToHost, m->stream));
+      HIPCHECK(hipStreamSynchronize(m->stream));
+      for (int k = 0; k < nsel; k++) out[dest[k]] = m->h_lp_rows[k];
+      continue;
+    }
     for (int r0 = 0; r0 < M; r0 += m->Rl) {
       int R = std::min(m->Rl, M - r0);
       lm_head_rows(m, M, r0, R, r0 > 0);

@@ -60,9 +60,11 @@ void launch_qkrope(hipStream_t s, const float* qkv, int n_part, size_t part_stri
                    const ModelDims& md, int M);
 
 // h += sum of n_part split-K partial sums (ascending order), then out = rmsnorm(h) * g in A-tile
-// layout (bf16 MFMA path).
+// layout (bf16 MFMA path).  rows != null: gather: output row i is made from row rows[i] of h /
+// parts (M = number of gathered rows).
 void launch_add_rmsnorm(hipStream_t s, float* h, const float* parts, int n_part, size_t part_stride,
-                        const bf16_t* g, bf16_t* out, int M, int H, float eps);
+                        const bf16_t* g, bf16_t* out, int M, int H, float eps,
+                        const int32_t* rows = nullptr);
 
 template <typename TA, typename TKV, bool SWZ>
 void launch_attention_generic(hipStream_t s, const TA* q, KvPool pool, const int32_t* row_pos,
@@ -74,7 +76,7 @@ template <typename TA>
 void launch_swiglu(hipStream_t s, const float* gu, TA* m, int M, int I, bool atile);
 
 // ---- MFMA kernels (bf16, head_dim 128) -------------------------------------------------------
-enum GemmEpilogue { EPI_STORE = 0, EPI_SWIGLU = 2 };
+enum GemmEpilogue { EPI_STORE = 0, EPI_SWIGLU = 2, EPI_LSE = 3 };
 // A: bf16 A-tile layout [ceil(M/128)*128, K]; Wp: repacked weights (see repack kernel).
 // EPI_STORE: split-K slice z writes its fp32 partial sum to C + z * M * N (row-major [M, N]); the
 // consumer adds the `splits` partials.  EPI_SWIGLU (splits = 1): C is bf16 A-tile [.., N/2], gate
@@ -82,6 +84,11 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_SWIGLU = 2 };
 // K % 64 == 0, N % 32 == 0.  Returns the number of splits actually used.
 int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, int M, int N,
                      int K, int epilogue, int splits, int nw);
+// lm-head fused with the log-softmax of the masked log-prob pass: for each of the M rows of A
+// (bf16 A-tile layout) lp[row] = log softmax(z / T)[tgt[row]] with z = A[row] . Wp^T (V logits, never
+// stored) and scale_c = log2(e) / T.  part: scratch of M * (V / 32) float pairs; zt: M floats.
+void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, int M, int V, int K,
+                            const int32_t* tgt, float scale_c, float* part, float* zt, float* lp);
 // W[N,K] row-major -> operand strips.  interleave16: rows come from two matrices Wg, Wu
 // ([N/2,K] each) interleaved in groups of 16 (gate, up, gate, up, ...).
 void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16_t* Wp, int N,

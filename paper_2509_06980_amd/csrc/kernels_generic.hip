@@ -46,9 +46,11 @@ __global__ void rmsnorm_kernel(const float* __restrict__ h, const TW* __restrict
 // grid M, block 256: h[row] += sum_p parts[p][row]; out = rmsnorm(h[row]) * g, A-tile layout
 __global__ void add_rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ parts, int n_part,
                                    size_t part_stride, const bf16_t* __restrict__ g,
-                                   bf16_t* __restrict__ out, int H, float eps) {
+                                   bf16_t* __restrict__ out, int H, float eps,
+                                   const int32_t* __restrict__ rows) {
   __shared__ float red[4];
-  int row = blockIdx.x;
+  const int orow = blockIdx.x;
+  const int row = rows ? rows[orow] : orow;
   float* x = h + (size_t)row * H;
   const float* pr = parts + (size_t)row * H;
   float ss = 0.f;
@@ -84,13 +86,13 @@ __global__ void add_rmsnorm_kernel(float* __restrict__ h, const float* __restric
       float y1 = x[j + 2 * e + 1] * inv * bf2f(g[j + 2 * e + 1]);
       w[e] = (uint32_t)f2bf(y0) | ((uint32_t)f2bf(y1) << 16);
     }
-    *(uint4*)(out + atile_off(row, j, H)) = make_uint4(w[0], w[1], w[2], w[3]);
+    *(uint4*)(out + atile_off(orow, j, H)) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
 void launch_add_rmsnorm(hipStream_t s, float* h, const float* parts, int n_part, size_t part_stride,
-                        const bf16_t* g, bf16_t* out, int M, int H, float eps) {
-  if (M > 0) add_rmsnorm_kernel<<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps);
+                        const bf16_t* g, bf16_t* out, int M, int H, float eps, const int32_t* rows) {
+  if (M > 0) add_rmsnorm_kernel<<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
 }
 
 template <typename TA, typename TW>

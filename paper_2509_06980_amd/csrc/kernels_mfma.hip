@@ -50,12 +50,19 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 // HBM into registers, D chunks ahead.  blockIdx.z selects a K-slice (split-K); every slice
 // stores its own fp32 partial sum, which the consumer kernel adds in a fixed order (no atomics:
 // results are bit-reproducible).
+// EPI_LSE (lm-head of the masked log-prob pass): the product is formed transposed (weights as the
+// MFMA row operand; both operands have the same lane layout, so swapping them costs nothing), which
+// puts 16 vocabulary entries of one batch row into the registers of a lane.  The epilogue reduces
+// its 32-column strip per row to (max, sum of 2^((z - max) c)) and picks out the target token's
+// logit; the logits themselves are never stored.
 // =============================================================================================
 template <int EPI, int D, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ Wp,
                                                             void* __restrict__ Cv, int M, int N,
-                                                            int K, int chunks_per_split) {
+                                                            int K, int chunks_per_split,
+                                                            const int32_t* __restrict__ tgt,
+                                                            float* __restrict__ zt, float scale_c) {
   constexpr int NT = 64 * NW;        // threads
   constexpr int APT = 1024 / NT;     // 16-byte pieces of an A chunk per thread
   __shared__ u32x4 As[2][1024];
@@ -112,7 +119,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
       bf16x8 b = __builtin_bit_cast(bf16x8, bcur[kk]);                      \
       _Pragma("unroll") for (int mb = 0; mb < 4; mb++) {                    \
         bf16x8 a = __builtin_bit_cast(bf16x8, av[kk * 4 + mb]);             \
-        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0); \
+        acc[mb] = EPI == EPI_LSE                                            \
+                      ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[mb], 0, 0, 0) \
+                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[mb], 0, 0, 0); \
       }                                                                     \
     }                                                                       \
   }
@@ -131,6 +140,34 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
 #undef GEMM_LOAD
 #undef GEMM_STAGE
   if (!active) return;
+  if (EPI == EPI_LSE) {
+    // acc[mb][i] = z[batch row mb*32 + lane%32][vocab nb*32 + (i/4)*8 + (lane/32)*4 + i%4]
+    float2* P = (float2*)Cv;
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++) {
+      const int row = mt * 128 + mb * 32 + (lane & 31);
+      float mx = acc[mb][0];
+#pragma unroll
+      for (int i = 1; i < 16; i++) mx = fmaxf(mx, acc[mb][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float sm = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; i++) sm += exp2f((acc[mb][i] - mx) * scale_c);
+      sm += __shfl_xor(sm, 32, 64);
+      if (row < M) {
+        if (lane < 32) P[(size_t)row * NB + nb] = make_float2(mx, sm);
+        const int t = tgt[row];
+        if ((t >> 5) == nb && ((t >> 2) & 1) == (lane >> 5)) {
+          const int isel = ((t & 31) >> 3) * 4 + (t & 3);
+          float z = acc[mb][0];
+#pragma unroll
+          for (int i = 1; i < 16; i++) z = isel == i ? acc[mb][i] : z;
+          zt[row] = z;
+        }
+      }
+    }
+    return;
+  }
   const int col = nb * 32 + (lane & 31);
   float* Cp = (float*)Cv + (size_t)blockIdx.z * M * N;
 #pragma unroll
@@ -157,9 +194,9 @@ template <int D, int NW>
 static void gemm_launch(hipStream_t s, dim3 grid, const bf16_t* A, const bf16_t* Wp, void* C, int M,
                         int N, int K, int epilogue, int cps) {
   if (epilogue == EPI_STORE)
-    gemm_mfma_kernel<EPI_STORE, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps);
+    gemm_mfma_kernel<EPI_STORE, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps, nullptr, nullptr, 0.f);
   else
-    gemm_mfma_kernel<EPI_SWIGLU, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps);
+    gemm_mfma_kernel<EPI_SWIGLU, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps, nullptr, nullptr, 0.f);
 }
 
 // depth = chunks in flight per workgroup (2 or 4)
@@ -183,6 +220,43 @@ int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, 
                      int K, int epilogue, int splits, int nw) {
   // two chunks in flight: fewer registers, more resident workgroups (measured best at M = 128)
   return launch_gemm_mfma_cfg(s, A, Wp, C, M, N, K, epilogue, splits, nw, 2);
+}
+
+// One workgroup per row: combine the per-strip (max, sum) pairs in a fixed order and write
+// log softmax(z / T)[target] = (z_t - max) c ln2 - ln sum, c = log2(e) / T.
+__global__ __launch_bounds__(256) void lse_finish_kernel(const float2* __restrict__ P,
+                                                         const float* __restrict__ zt, int NB,
+                                                         float scale_c, float* __restrict__ lp) {
+  __shared__ float red[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const float2* p = P + (size_t)row * NB;
+  float mx = -3.0e38f;
+  for (int j = tid; j < NB; j += 256) mx = fmaxf(mx, p[j].x);
+  mx = wave_max(mx);
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sm = 0.f;
+  for (int j = tid; j < NB; j += 256) {
+    float2 v = p[j];
+    sm += v.y * exp2f((v.x - mx) * scale_c);
+  }
+  sm = wave_sum(sm);
+  if ((tid & 63) == 0) red[tid >> 6] = sm;
+  __syncthreads();
+  if (tid == 0) {
+    float S = (red[0] + red[1]) + (red[2] + red[3]);
+    lp[row] = (zt[row] - mx) * scale_c * 0.6931471805599453f - logf(S);
+  }
+}
+
+void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, int M, int V, int K,
+                            const int32_t* tgt, float scale_c, float* part, float* zt, float* lp) {
+  if (M <= 0) return;
+  dim3 grid((V + 127) / 128, (M + 127) / 128, 1);
+  gemm_mfma_kernel<EPI_LSE, 2, 4><<<grid, 256, 0, s>>>(A, Wp, part, M, V, K, K / 64, tgt, zt, scale_c);
+  lse_finish_kernel<<<M, 256, 0, s>>>((const float2*)part, zt, V / 32, scale_c, lp);
 }
 
 // =============================================================================================

@@ -294,6 +294,38 @@ def test_recompute_over_several_lm_head_passes():
     assert np.count_nonzero(rec) == 6 and np.count_nonzero(ref) == 6
 
 
+def test_fused_logprob_pass_many_sampled_rows_and_temperature():
+    # the masked log-prob pass gathers the rows whose target was sampled, runs the lm-head with the
+    # log-softmax reduced in its epilogue and never stores logits: > 128 sampled rows (several row
+    # tiles, ragged tail), interleaved with appended chunks, at a temperature other than 1
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=12, weight_std=0.03, gain_std=0.1)
+    o, g = _pair(shape, blob, max_context=512, max_trajectories=4, kv_pool_pages=100)
+    rng = np.random.default_rng(6)
+    toks0 = rng.integers(0, shape.vocab, 50)
+    obs = rng.integers(0, shape.vocab, 2 * 19)
+    for e in (o, g):
+        e.append_observation([3, 1], toks0, [33, 17])
+    for turn in range(2):
+        for _ in range(37):
+            ids, lps = o.decode_step([3, 1], 0.7, 21)
+            glp = g.decode_step_forced([3, 1], 0.7, ids)
+            assert np.abs(glp - lps).max() < TOL_BF16
+        if turn == 0:
+            for e in (o, g):
+                e.append_observation([3, 1], obs, [19, 19])
+    ref, rec = o.recompute_logprobs([1, 3], 0.7), g.recompute_logprobs([1, 3], 0.7)
+    assert rec.shape == ref.shape == (50 + 38 + 4 * 37,)
+    assert np.abs(rec - ref).max() < TOL_BF16
+    mask = np.concatenate([o.traj_read(1)[1], o.traj_read(3)[1]])
+    assert np.count_nonzero(mask == 0) == 148 and np.all(rec[mask == 1] == 0.0)
+    # the recomputed values are the log-probs reported at generation time
+    gen = np.concatenate([g.traj_read(1)[2], g.traj_read(3)[2]])
+    assert np.abs(rec - gen)[mask == 0].max() < TOL_BF16
+    # greedy convention: temperature 0 reports the T = 1 distribution
+    assert np.array_equal(g.recompute_logprobs([1, 3], 0.0), g.recompute_logprobs([1, 3], 1.0))
+
+
 def test_full_size_cfg2_shape_sampled_trajectories():
     """Qwen3-0.6B shape (GQA group 2, 28 layers), 64 trajectories as in cfg2: two trajectories are
     followed by the oracle, teacher-forcing the GPU with the oracle's ids."""
