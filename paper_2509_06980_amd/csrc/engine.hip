@@ -571,7 +571,8 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   int max_pages = (rt->max_context + RL_PAGE - 1) / RL_PAGE;
   m->md = ModelDims{c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads, c.head_dim, c.intermediate,
                     c.vocab, c.rms_eps, c.qk_norm, max_pages};
-  m->rows_per_item = m->mfma ? 4 * (16 / (c.n_q_heads / c.n_kv_heads)) : 1;   // prefill items: 4 waves x 16/G rows
+  // prefill items: 4 waves x RL_PREFILL_CB column blocks x 16/G rows
+  m->rows_per_item = m->mfma ? 4 * RL_PREFILL_CB * (16 / (c.n_q_heads / c.n_kv_heads)) : 1;
   int rc = RL_OK;
 #define TRY(x) do { rc = (x); if (rc) { rl_model_free(m); return rc; } } while (0)
 #define HIPTRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fail(RL_E_HIP, std::string(#x) + ": " + hipGetErrorString(e_)); rl_model_free(m); return RL_E_HIP; } } while (0)

@@ -97,7 +97,11 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 // paged GQA attention over work items; q bf16 row-major [M, nq*128]; o bf16 A-tile [.., nq*128].
 // Decode (prefill = false): single-row items, possibly cut into parts; scratch: fp32
 // [part slots][nkv][16 * 130] for items with part >= 0, merged by `merges`.
-// Prefill: items of up to 4 * 16/G consecutive rows of one trajectory, one part each.
+// Prefill: items of up to 4 * RL_PREFILL_CB * 16/G consecutive rows of one trajectory (G = n_q /
+// n_kv), one part each.
+#ifndef RL_PREFILL_CB
+#define RL_PREFILL_CB 2   // 16-column blocks per wave of the prefill kernel (2: still two waves per SIMD)
+#endif
 void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
                            int n_items, const AttnMerge* merges, int n_merges,
                            const int32_t* page_table, bf16_t* o, float* scratch,

@@ -441,10 +441,71 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   }
 }
 
-// Chunked prefill: one workgroup per (item of up to 4 * 16/G rows, kv head).  Wave w owns the
-// item's rows [w * 16/G, (w+1) * 16/G) with all G heads of the group as its 16 MFMA columns and
-// walks every page those rows may see; the four waves read the same pages at about the same time,
-// so keys / values come from HBM once per 4 * 16/G query rows.  No cross-wave merge is needed.
+// One page of the prefill kernel's online softmax for the CB column blocks of a wave.  The scores
+// stay unscaled until the exponent: 2^(S c - max c) is one fused multiply-add per score.  MASKED:
+// the page may hold keys behind some row's position (pages on the causal diagonal, and every page
+// for columns past the item's rows, whose position is -1).
+template <int CB, bool MASKED>
+__device__ __forceinline__ void prefill_page(const u32x4 (&KR)[4], const u32x4 (&VR)[4], int pg,
+                                             const u32x4 (&qreg)[CB][4], f32x4 (&acc)[CB][8],
+                                             float (&m)[CB], float (&l)[CB], const int (&mypos)[CB],
+                                             int g, float scale2) {
+#pragma unroll
+  for (int cb = 0; cb < CB; cb++) {
+    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; c++)
+      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KR[c]),
+                                                  __builtin_bit_cast(bf16x8, qreg[cb][c]), S, 0, 0, 0);
+    bool vis[4];
+    float mx = ATT_NEG;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      vis[i] = !MASKED || pg * RL_PAGE + 4 * g + i <= mypos[cb];
+      mx = fmaxf(mx, vis[i] ? S[i] : ATT_NEG);
+    }
+    mx = quad_max(mx);
+    // m is kept in scaled units (score * scale2); scale2 > 0, so the maximum commutes with it
+    const float mn = fmaxf(m[cb], mx * scale2);
+    if (__any(mn > m[cb])) {
+      const float alpha = exp2f(m[cb] - mn);
+      l[cb] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 8; j++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) acc[cb][j][i] *= alpha;
+      m[cb] = mn;
+    }
+    float p[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], scale2, -mn));
+      if (MASKED) p[i] = vis[i] ? p[i] : 0.f;
+    }
+    l[cb] += (p[0] + p[1]) + (p[2] + p[3]);
+    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+    bf16x4_t pb4 = {(__bf16)p[0], (__bf16)p[1], (__bf16)p[2], (__bf16)p[3]};
+    const s16x4 pb = __builtin_bit_cast(s16x4, pb4);
+#pragma unroll
+    for (int jp = 0; jp < 4; jp++) {
+      typedef __attribute__((__vector_size__(2 * sizeof(unsigned int)))) unsigned int u32x2_t;
+      const u32x2_t lo = {VR[jp][0], VR[jp][1]}, hi = {VR[jp][2], VR[jp][3]};
+      acc[cb][2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pb,
+                                                                   acc[cb][2 * jp], 0, 0, 0);
+      acc[cb][2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pb,
+                                                                       acc[cb][2 * jp + 1], 0, 0, 0);
+    }
+  }
+}
+
+// Chunked prefill: one workgroup per (item of up to 4 * CB * 16/G rows, kv head).  Wave w owns
+// CB * 16/G consecutive rows of the item as CB blocks of 16 MFMA columns (16/G rows x the G heads
+// of the group) and walks every page those rows may see.  A page's keys / values are loaded into
+// registers once per wave and used by all CB column blocks, so every byte fetched feeds CB * 16
+// columns; the four waves read the same pages at about the same time (the later copies hit in
+// cache).  The running output is rescaled only on pages where some column's maximum moved.
+// No cross-wave merge is needed.
+template <int CB>
 __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kpool, const bf16_t* __restrict__ vpool,
     const AttnItem* __restrict__ items, const int32_t* __restrict__ page_table,
@@ -454,42 +515,78 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
   const int kvh = blockIdx.x - item_idx * nkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, n = lane & 15, hq = n & ((1 << gshift) - 1);
-  const int rpw = 16 >> gshift;                       // rows per wave
-  const int r = wave * rpw + (n >> gshift);           // row within the item
-  const bool colvalid = r < it.nrows;
-  const int mypos = it.pos0 + r;
-  const int wave_rows = min(it.nrows - wave * rpw, rpw);
+  const int rpb = 16 >> gshift;                       // rows per column block
+  const int wrow0 = wave * CB * rpb;                  // first row of this wave within the item
+  const int wave_rows = min(it.nrows - wrow0, CB * rpb);
   const int pg0 = 0;
-  const int pg1 = wave_rows > 0 ? (it.pos0 + wave * rpw + wave_rows - 1) / RL_PAGE + 1 : 0;
+  const int pg1 = wave_rows > 0 ? (it.pos0 + wrow0 + wave_rows - 1) / RL_PAGE + 1 : 0;
   const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
-  u32x4 qreg[4];
+  u32x4 qreg[CB][4];
+  f32x4 acc[CB][8];
+  float m[CB], l[CB];
+  int mypos[CB];
 #pragma unroll
-  for (int c = 0; c < 4; c++) {
-    qreg[c] = (u32x4){0u, 0u, 0u, 0u};
-    if (colvalid)
-      qreg[c] = *(const u32x4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
+  for (int cb = 0; cb < CB; cb++) {
+    const int r = wrow0 + cb * rpb + (n >> gshift);
+    // columns past the item's rows get position -1: every key is masked for them
+    mypos[cb] = r < it.nrows ? it.pos0 + r : -1;
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      qreg[cb][c] = (u32x4){0u, 0u, 0u, 0u};
+      if (r < it.nrows)
+        qreg[cb][c] = *(const u32x4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc[cb][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    m[cb] = ATT_NEG;
+    l[cb] = 0.f;
   }
-  f32x4 acc[8];
-#pragma unroll
-  for (int j = 0; j < 8; j++) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m = ATT_NEG, l = 0.f;
   const int pglast = max(pg1 - 1, pg0);
   const size_t head_off = (size_t)kvh * 2048 + lane * 8;
   u32x4 kA[4], vA[4], kB[4], vB[4];
-  ATT_PAGE_LOOP
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-  if (colvalid) {
-    // acc[jb][i] is O[row r][head hq][d = 16 jb + 4 g + i]: four consecutive dims = one 8-byte store
-    const float inv = 1.0f / l;
-    const size_t base = atile_off(it.row0 + r, ((kvh << gshift) + hq) * 128 + 4 * g, nq * 128);
+  // pages that end at or before the wave's first row are visible to all of its rows: no masking
+  const int full_pages = (it.pos0 + wrow0 + 1) / RL_PAGE;
+#define PF_PAGE(KR, VR, PG)                                                   \
+  {                                                                           \
+    if ((PG) < full_pages)                                                    \
+      prefill_page<CB, false>(KR, VR, (PG), qreg, acc, m, l, mypos, g, scale2); \
+    else if ((PG) < pg1)                                                      \
+      prefill_page<CB, true>(KR, VR, (PG), qreg, acc, m, l, mypos, g, scale2); \
+  }
+  if (pg0 < pg1) {
+    int id_cur = pt[pg0];
+    int id_nxt = pt[min(pg0 + 1, pglast)];
+    ATT_LOAD(kA, vA, id_cur)
+    for (int pg = pg0; pg < pg1; pg += 2) {
+      int id_n2 = pt[min(pg + 2, pglast)];
+      ATT_LOAD(kB, vB, id_nxt)
+      __builtin_amdgcn_sched_barrier(0);
+      PF_PAGE(kA, vA, pg)
+      __builtin_amdgcn_sched_barrier(0);
+      id_nxt = pt[min(pg + 3, pglast)];
+      ATT_LOAD(kA, vA, id_n2)
+      __builtin_amdgcn_sched_barrier(0);
+      PF_PAGE(kB, vB, pg + 1)
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#undef PF_PAGE
 #pragma unroll
-    for (int jb = 0; jb < 8; jb++) {
-      uint2 w;
-      w.x = (uint32_t)f2bf(acc[jb][0] * inv) | ((uint32_t)f2bf(acc[jb][1] * inv) << 16);
-      w.y = (uint32_t)f2bf(acc[jb][2] * inv) | ((uint32_t)f2bf(acc[jb][3] * inv) << 16);
-      // k advances by 16 per jb: two A-tile k-blocks of 16 per 32 dims => +1 k-block each step
-      *(uint2*)(o + base + (size_t)jb * (4 * 64 * 8)) = w;
+  for (int cb = 0; cb < CB; cb++) {
+    const float lt = quad_sum(l[cb]);
+    const int r = wrow0 + cb * rpb + (n >> gshift);
+    if (r < it.nrows) {
+      // acc[jb][i] is O[row r][head hq][d = 16 jb + 4 g + i]: four consecutive dims = one 8-byte store
+      const float inv = 1.0f / lt;
+      const size_t base = atile_off(it.row0 + r, ((kvh << gshift) + hq) * 128 + 4 * g, nq * 128);
+#pragma unroll
+      for (int jb = 0; jb < 8; jb++) {
+        uint2 w;
+        w.x = (uint32_t)f2bf(acc[cb][jb][0] * inv) | ((uint32_t)f2bf(acc[cb][jb][1] * inv) << 16);
+        w.y = (uint32_t)f2bf(acc[cb][jb][2] * inv) | ((uint32_t)f2bf(acc[cb][jb][3] * inv) << 16);
+        // k advances by 16 per jb: two A-tile k-blocks of 16 per 32 dims => +1 k-block each step
+        *(uint2*)(o + base + (size_t)jb * (4 * 64 * 8)) = w;
+      }
     }
   }
 }
@@ -528,7 +625,7 @@ void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const At
   int gshift = 0;
   while ((1 << gshift) < md.nq / md.nkv) gshift++;
   if (prefill) {
-    attention_prefill_mfma_kernel<<<n_items * md.nkv, 256, 0, s>>>(
+    attention_prefill_mfma_kernel<RL_PREFILL_CB><<<n_items * md.nkv, 256, 0, s>>>(
         q, (const bf16_t*)pool.k, (const bf16_t*)pool.v, items, page_table, o, md.nq, md.nkv, gshift,
         md.max_pages_per_traj, scale2);
     return;

@@ -75,6 +75,30 @@ __device__ __forceinline__ int vblk_off(int tok, int d, int D) {
   return SWZ ? vswz_off(tok, d) : tok * D + d;
 }
 
+// Reductions over the four lanes {n, n + 16, n + 32, n + 48} (the four token groups of one MFMA
+// column) with the gfx950 row-swap instructions: swapping a register with itself puts lanes
+// i and i ^ 16 (i ^ 32) side by side; every lane ends with the result.  Plain VALU, no LDS path.
+__device__ __forceinline__ float quad_max(float x) {
+  unsigned a = __builtin_bit_cast(unsigned, x);
+  auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+  unsigned r0 = r[0], r1 = r[1];
+  float y = fmaxf(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
+  unsigned b = __builtin_bit_cast(unsigned, y);
+  auto q = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  unsigned q0 = q[0], q1 = q[1];
+  return fmaxf(__builtin_bit_cast(float, q0), __builtin_bit_cast(float, q1));
+}
+__device__ __forceinline__ float quad_sum(float x) {
+  unsigned a = __builtin_bit_cast(unsigned, x);
+  auto r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+  unsigned r0 = r[0], r1 = r[1];
+  float y = __builtin_bit_cast(float, r0) + __builtin_bit_cast(float, r1);
+  unsigned b = __builtin_bit_cast(unsigned, y);
+  auto q = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  unsigned q0 = q[0], q1 = q[1];
+  return __builtin_bit_cast(float, q0) + __builtin_bit_cast(float, q1);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
