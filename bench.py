@@ -140,6 +140,37 @@ def append_mfma(stats, shape):
             "note": "algorithmic flops of all appends / wall time inside rl_append_observation and rl_fork"}
 
 
+def tool_loop_bench(rl, blob, shape, args):
+    """Generate / Invoke / Update loop with asynchronous (mock) tools: tokens/s of the continuous-
+    batching scheduler and of the synchronous turn-barrier baseline on the same plans."""
+    from paper_2509_06980_amd.tool_loop import MockTools, ToolLoop, TrajectoryPlan
+    from synthetic.workloads import tool_loop_plans
+
+    def sc(x):
+        return max(1, int(round(x * args.scale)))
+    raw, longest = tool_loop_plans(shape.vocab, 128, sc(512), (1, 6), (sc(32), sc(512)),
+                                   (sc(64), sc(1024)), sc(8192))
+    plans = [TrajectoryPlan(i, p, t) for i, p, t in raw]
+    res = {"plans": "128 trajectories, prompt 512, turns U{1..6}, gen U{32..512}, obs U{64..1024} (x scale), "
+                    "tool latency U%s ms on worker threads" % (tuple(args.tool_latency_ms),)}
+    for policy in ("continuous", "lockstep"):
+        eng = rl.RolloutEngine(blob, max_context=longest + 16, max_trajectories=128,
+                               kv_pool_pages=128 * (longest // 16 + 2) + 64)
+        tools = MockTools(shape.vocab, seed=5, latency=tuple(args.tool_latency_ms), clock="wall", workers=32)
+        _, st = ToolLoop(eng, plans, tools, temperature=1.0, rng_seed=3).run(policy)
+        tools.close()
+        eng.close()
+        res[policy] = {"tokens_per_s": round(st["generated"] / st["wall_s"], 1),
+                       "wall_s": round(st["wall_s"], 2), "decode_steps": st["decode_steps"],
+                       "mean_batch": round(st["mean_batch"], 1), "append_calls": st["append_calls"],
+                       "gpu_idle_wait_s": round(st["wait_s"], 2), "decode_s": round(st["decode_s"], 2),
+                       "append_s": round(st["append_s"], 2)}
+        print(f"[bench] tool loop {policy}: {res[policy]}", file=sys.stderr, flush=True)
+    res["speedup_continuous_over_lockstep"] = round(
+        res["continuous"]["tokens_per_s"] / res["lockstep"]["tokens_per_s"], 3)
+    return res
+
+
 def cpu_baseline(blob, shape, budget_note):
     """Time the CPU oracle (as is) on a small slice of the same workload."""
     from oracle import OracleEngine
@@ -175,6 +206,10 @@ def main():
                     help="shrink every length of the workload (development only; not a valid headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--timing-every", type=int, default=16)
+    ap.add_argument("--tool-loop", action="store_true",
+                    help="also run the ragged 128-trajectory mix against the mock tool layer (wall-clock "
+                         "latencies), continuous batching vs. the turn-barrier baseline")
+    ap.add_argument("--tool-latency-ms", type=float, nargs=2, default=(100.0, 2000.0))
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU: trajectories are independent, so more GPUs "
@@ -270,6 +305,9 @@ def main():
         "decode_s_per_step": round(stats["decode_s"] / max(args.steps, 1), 3),
         "roofline": roofline,
     }
+    if args.tool_loop:
+        eng.close()
+        out["tool_loop"] = tool_loop_bench(rl, blob, shape, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(blob, shape, "baseline only, not the target")
     print(json.dumps(out), flush=True)

@@ -72,18 +72,10 @@ def uniform_turns(name, vocab, n_traj, prompt_len, n_turns, gen_len, obs_len,
     return w
 
 
-def ragged_turns(name, vocab, n_traj, prompt_len, turns_range, gen_range, obs_range,
-                 max_context, temperature, token_seed=2, rng_seed=3, length_seed=4):
-    """Per-trajectory turn counts and lengths; trajectories leave the batch as they finish."""
-    rng = np.random.default_rng(token_seed)
-    lrng = np.random.default_rng(length_seed)
-    w = Workload(name, vocab, n_trajectories=n_traj)
-    ids = np.arange(n_traj, dtype=np.int32)
-    w.events.append(("append", ids.copy(), _tok(rng, n_traj * prompt_len, vocab),
-                     np.full(n_traj, prompt_len, np.int32)))
-    w.n_prompt = n_traj * prompt_len
-    # schedule[i] = list of (gen, obs) clipped so the context never exceeds max_context
-    sched = []
+def ragged_schedule(lrng, n_traj, prompt_len, turns_range, gen_range, obs_range, max_context):
+    """schedule[i] = list of (gen, obs) turns of trajectory i, clipped so that its context never
+    exceeds max_context; the last turn has obs = 0.  Returns (schedule, longest context)."""
+    sched, longest = [], 0
     for _ in range(n_traj):
         nt = int(lrng.integers(turns_range[0], turns_range[1] + 1))
         ctx, turns = prompt_len, []
@@ -100,7 +92,35 @@ def ragged_turns(name, vocab, n_traj, prompt_len, turns_range, gen_range, obs_ra
             if o == 0:
                 break
         sched.append(turns)
-        w.max_context = max(w.max_context, ctx)
+        longest = max(longest, ctx)
+    return sched, longest
+
+
+def tool_loop_plans(vocab, n_traj, prompt_len, turns_range, gen_range, obs_range, max_context,
+                    token_seed=2, length_seed=4):
+    """Per-trajectory plans for a scheduler that talks to a (mock) tool layer: the same ragged
+    length mix as `ragged_turns`, but the observation tokens come from the tool layer at run time.
+    Returns ([(traj_id, prompt_tokens, [(gen, obs), ...])], longest context)."""
+    rng = np.random.default_rng(token_seed)
+    lrng = np.random.default_rng(length_seed)
+    prompts = _tok(rng, n_traj * prompt_len, vocab).reshape(n_traj, prompt_len)
+    sched, longest = ragged_schedule(lrng, n_traj, prompt_len, turns_range, gen_range, obs_range,
+                                     max_context)
+    return [(i, prompts[i].copy(), sched[i]) for i in range(n_traj)], longest
+
+
+def ragged_turns(name, vocab, n_traj, prompt_len, turns_range, gen_range, obs_range,
+                 max_context, temperature, token_seed=2, rng_seed=3, length_seed=4):
+    """Per-trajectory turn counts and lengths; trajectories leave the batch as they finish."""
+    rng = np.random.default_rng(token_seed)
+    lrng = np.random.default_rng(length_seed)
+    w = Workload(name, vocab, n_trajectories=n_traj)
+    ids = np.arange(n_traj, dtype=np.int32)
+    w.events.append(("append", ids.copy(), _tok(rng, n_traj * prompt_len, vocab),
+                     np.full(n_traj, prompt_len, np.int32)))
+    w.n_prompt = n_traj * prompt_len
+    sched, w.max_context = ragged_schedule(lrng, n_traj, prompt_len, turns_range, gen_range,
+                                           obs_range, max_context)
     turn_idx = [0] * n_traj
     left = [s[0][0] if s else 0 for s in sched]
     active = [i for i in range(n_traj) if sched[i]]
