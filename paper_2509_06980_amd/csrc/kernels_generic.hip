@@ -90,9 +90,75 @@ __global__ void add_rmsnorm_kernel(float* __restrict__ h, const float* __restric
   }
 }
 
+// Same operation with the whole row in registers: every load of the row and of its (up to 8)
+// partial sums is issued before the first use, so a row costs about one memory round trip instead
+// of one per group of partials; the normalised row is written from registers.  H <= ITER * 1024.
+template <int ITER>
+__global__ __launch_bounds__(256) void add_rmsnorm_reg_kernel(
+    float* __restrict__ h, const float* __restrict__ parts, int n_part, size_t part_stride,
+    const bf16_t* __restrict__ g, bf16_t* __restrict__ out, int H, float eps,
+    const int32_t* __restrict__ rows) {
+  __shared__ float red[4];
+  const int orow = blockIdx.x;
+  const int row = rows ? rows[orow] : orow;
+  float* x = h + (size_t)row * H;
+  const float* pr = parts + (size_t)row * H;
+  float4 v[ITER], u[ITER][8];
+  uint2 gw[ITER];
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int j = threadIdx.x * 4 + it * 1024;
+    const bool ok = j < H;
+    v[it] = ok ? *(const float4*)(x + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+    gw[it] = ok ? *(const uint2*)(g + j) : make_uint2(0u, 0u);
+#pragma unroll
+    for (int p = 0; p < 8; p++)
+      u[it][p] = (ok && p < n_part) ? *(const float4*)(pr + (size_t)p * part_stride + j)
+                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+#pragma unroll
+    for (int p = 0; p < 8; p++)
+      if (p < n_part) {   // ascending order, as the looping kernel adds them
+        v[it].x += u[it][p].x; v[it].y += u[it][p].y; v[it].z += u[it][p].z; v[it].w += u[it][p].w;
+      }
+    const int j = threadIdx.x * 4 + it * 1024;
+    if (n_part > 0 && j < H) *(float4*)(x + j) = v[it];
+    ss += v[it].x * v[it].x + v[it].y * v[it].y + v[it].z * v[it].z + v[it].w * v[it].w;
+  }
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + eps);
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int j = threadIdx.x * 4 + it * 1024;
+    if (j < H) {
+      float y0 = v[it].x * inv * bf2f((bf16_t)(gw[it].x & 0xffff));
+      float y1 = v[it].y * inv * bf2f((bf16_t)(gw[it].x >> 16));
+      float y2 = v[it].z * inv * bf2f((bf16_t)(gw[it].y & 0xffff));
+      float y3 = v[it].w * inv * bf2f((bf16_t)(gw[it].y >> 16));
+      uint2 w;
+      w.x = (uint32_t)f2bf(y0) | ((uint32_t)f2bf(y1) << 16);
+      w.y = (uint32_t)f2bf(y2) | ((uint32_t)f2bf(y3) << 16);
+      *(uint2*)(out + atile_off(orow, j, H)) = w;   // 4 consecutive k share one 16-byte lane slot
+    }
+  }
+}
+
 void launch_add_rmsnorm(hipStream_t s, float* h, const float* parts, int n_part, size_t part_stride,
                         const bf16_t* g, bf16_t* out, int M, int H, float eps, const int32_t* rows) {
-  if (M > 0) add_rmsnorm_kernel<<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
+  if (M <= 0) return;
+  if (n_part <= 8 && H % 4 == 0 && H <= 4096) {
+    if (H <= 1024) add_rmsnorm_reg_kernel<1><<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
+    else if (H <= 2048) add_rmsnorm_reg_kernel<2><<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
+    else if (H <= 3072) add_rmsnorm_reg_kernel<3><<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
+    else add_rmsnorm_reg_kernel<4><<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
+    return;
+  }
+  add_rmsnorm_kernel<<<M, 256, 0, s>>>(h, parts, n_part, part_stride, g, out, H, eps, rows);
 }
 
 template <typename TA, typename TW>
@@ -303,12 +369,102 @@ void launch_gemm_generic(hipStream_t s, const TA* A, const TW* W, float* C, int 
 template void launch_gemm_generic<float, float>(hipStream_t, const float*, const float*, float*, int, int, int, bool);
 template void launch_gemm_generic<bf16_t, bf16_t>(hipStream_t, const bf16_t*, const bf16_t*, float*, int, int, int, bool);
 
+// head_dim 128, bf16, MFMA cache layout: grid (M, ceil(heads / 16)), block 256.  Sixteen lanes
+// own one head: lane `sub` holds dims 4 sub .. 4 sub + 3 and their rotate-half partners 64 + ...,
+// so partial sums arrive as 16-byte loads (all issued before the first add) and q, k leave as
+// 8-byte stores.
+__global__ __launch_bounds__(256) void qkrope128_kernel(
+    const float* __restrict__ qkv, int n_part, size_t part_stride, const bf16_t* __restrict__ gq,
+    const bf16_t* __restrict__ gk, const float* __restrict__ rope_cs,
+    const int32_t* __restrict__ row_pos, const int32_t* __restrict__ row_slot,
+    const int32_t* __restrict__ page_table, bf16_t* __restrict__ qout, bf16_t* __restrict__ kpool,
+    bf16_t* __restrict__ vpool, int nq, int nkv, float eps, int qk_norm, int pt_stride) {
+  const int row = blockIdx.x, sub = threadIdx.x & 15;
+  const int hd = blockIdx.y * 16 + (threadIdx.x >> 4), NH = nq + 2 * nkv;
+  if (hd >= NH) return;          // whole 16-lane groups leave together; no barrier below
+  const int pos = row_pos[row];
+  const float* x = qkv + ((size_t)row * NH + hd) * 128 + sub * 4;
+  float4 lo[8], hi[8];
+#pragma unroll
+  for (int p = 0; p < 8; p++) {
+    lo[p] = p < n_part ? *(const float4*)(x + (size_t)p * part_stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+    hi[p] = p < n_part ? *(const float4*)(x + (size_t)p * part_stride + 64) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const bool is_q = hd < nq, is_v = hd >= nq + nkv;
+  const bf16_t* g = is_q ? gq : gk;
+  const uint2 glo = *(const uint2*)(g + sub * 4), ghi = *(const uint2*)(g + 64 + sub * 4);
+  const float* cs = rope_cs + ((size_t)pos * 64 + sub * 4) * 2;     // (cos, sin) pairs of 4 dims
+  const float4 cs0 = *(const float4*)cs, cs1 = *(const float4*)(cs + 4);
+  float a[4] = {lo[0].x, lo[0].y, lo[0].z, lo[0].w}, b[4] = {hi[0].x, hi[0].y, hi[0].z, hi[0].w};
+#pragma unroll
+  for (int p = 1; p < 8; p++)
+    if (p < n_part) {
+      a[0] += lo[p].x; a[1] += lo[p].y; a[2] += lo[p].z; a[3] += lo[p].w;
+      b[0] += hi[p].x; b[1] += hi[p].y; b[2] += hi[p].z; b[3] += hi[p].w;
+    }
+  float ss = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; e++) ss += a[e] * a[e] + b[e] * b[e];
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 16);
+  bf16_t* blk = nullptr;
+  const int tok = pos & (RL_PAGE - 1);
+  if (!is_q) {
+    const int page = page_table[(size_t)row_slot[row] * pt_stride + (pos >> 4)];
+    const int kvh = is_v ? hd - nq - nkv : hd - nq;
+    blk = (is_v ? vpool : kpool) + ((size_t)page * nkv + kvh) * (RL_PAGE * 128);
+  }
+  if (is_v) {
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      blk[vswz_off(tok, sub * 4 + e)] = f2bf(a[e]);
+      blk[vswz_off(tok, 64 + sub * 4 + e)] = f2bf(b[e]);
+    }
+    return;
+  }
+  if (qk_norm) {
+    const float inv = 1.0f / sqrtf(ss / 128.0f + eps);
+    const float gl[4] = {bf2f((bf16_t)(glo.x & 0xffff)), bf2f((bf16_t)(glo.x >> 16)),
+                         bf2f((bf16_t)(glo.y & 0xffff)), bf2f((bf16_t)(glo.y >> 16))};
+    const float gh[4] = {bf2f((bf16_t)(ghi.x & 0xffff)), bf2f((bf16_t)(ghi.x >> 16)),
+                         bf2f((bf16_t)(ghi.y & 0xffff)), bf2f((bf16_t)(ghi.y >> 16))};
+#pragma unroll
+    for (int e = 0; e < 4; e++) { a[e] = a[e] * inv * gl[e]; b[e] = b[e] * inv * gh[e]; }
+  }
+  const float c[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, sn[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+  uint32_t y1[4], y2[4];
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    y1[e] = f2bf(a[e] * c[e] - b[e] * sn[e]);
+    y2[e] = f2bf(b[e] * c[e] + a[e] * sn[e]);
+  }
+  const uint2 w1 = make_uint2(y1[0] | (y1[1] << 16), y1[2] | (y1[3] << 16));
+  const uint2 w2 = make_uint2(y2[0] | (y2[1] << 16), y2[2] | (y2[3] << 16));
+  if (is_q) {
+    bf16_t* dst = qout + ((size_t)row * nq + hd) * 128 + sub * 4;
+    *(uint2*)dst = w1;
+    *(uint2*)(dst + 64) = w2;
+  } else {   // 4 consecutive dims lie in one 8-element lane slot of the swizzled key block
+    *(uint2*)(blk + kswz_off(tok, sub * 4)) = w1;
+    *(uint2*)(blk + kswz_off(tok, 64 + sub * 4)) = w2;
+  }
+}
+
 template <typename TW, typename TA, typename TKV, bool SWZ>
 void launch_qkrope(hipStream_t s, const float* qkv, int n_part, size_t part_stride, const TW* gq,
                    const TW* gk, const float* rope_cs, const int32_t* row_pos,
                    const int32_t* row_slot, const int32_t* page_table, TA* qout, KvPool pool,
                    const ModelDims& md, int M) {
   if (M <= 0) return;
+  if constexpr (SWZ) {
+    if (md.d == 128 && n_part <= 8) {
+      dim3 grid128(M, (md.nq + 2 * md.nkv + 15) / 16);
+      qkrope128_kernel<<<grid128, 256, 0, s>>>(qkv, n_part, part_stride, gq, gk, rope_cs, row_pos, row_slot,
+                                               page_table, qout, (bf16_t*)pool.k, (bf16_t*)pool.v, md.nq,
+                                               md.nkv, md.eps, md.qk_norm, md.max_pages_per_traj);
+      return;
+    }
+  }
   dim3 grid(M, md.nq + 2 * md.nkv);
   qkrope_kernel<TW, TA, TKV, SWZ><<<grid, 64, 0, s>>>(
       qkv, n_part, part_stride, gq, gk, rope_cs, row_pos, row_slot, page_table, qout, (TKV*)pool.k,
