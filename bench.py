@@ -206,6 +206,8 @@ def main():
                     help="shrink every length of the workload (development only; not a valid headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--timing-every", type=int, default=16)
+    ap.add_argument("--shared-prefix-attention", action="store_true",
+                    help="decode attention reads a forked group's shared pages once per block of members")
     ap.add_argument("--tool-loop", action="store_true",
                     help="also run the ragged 128-trajectory mix against the mock tool layer (wall-clock "
                          "latencies), continuous batching vs. the turn-barrier baseline")
@@ -232,7 +234,8 @@ def main():
     pages = w.n_trajectories * ((w.max_context + 15) // 16 + 2) + 64
     t0 = time.perf_counter()
     eng = rl.RolloutEngine(blob, max_context=w.max_context + 16, max_trajectories=w.n_trajectories,
-                           kv_pool_pages=pages)
+                           kv_pool_pages=pages,
+                           flags=rl.FLAG_SHARED_PREFIX_ATTENTION if args.shared_prefix_attention else 0)
     t_load = time.perf_counter() - t0
     print(f"[bench] {args.config}: {w.description}; blob {blob.nbytes / 1e9:.2f} GB in {t_blob:.1f}s, "
           f"load {t_load:.1f}s, pool {pages} pages", file=sys.stderr, flush=True)
@@ -257,6 +260,8 @@ def main():
     step_gpu_ms, steps_timed = eng.timing_read_steps(reset=True)
     eng.timing_enable(0)
 
+    # read ceiling of this GPU with a plain streaming kernel (2 GiB, 10 passes)
+    stream_gbs = rl.measure_stream_read(1 << 31, 10)
     roofline = None
     if attn_n > 0:
         # algorithmic bytes = keys + values of the DISTINCT pages the step references (prompt pages
@@ -264,6 +269,7 @@ def main():
         achieved = attn_unique / (attn_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "frac_of_measured_stream_read": round(achieved / stream_gbs, 4),
                     "traffic": recorded_traffic(args.config) if args.scale == 1.0 else None,
                     "achieved_counting_shared_pages_per_trajectory": round(attn_bytes / (attn_ms * 1e-3) / 1e9, 1),
                     "kernel": "attention_mfma_kernel" if eng.config["head_dim"] == 128 and
@@ -280,11 +286,14 @@ def main():
                    "trajectories": w.n_trajectories, "generated_tokens_per_step": w.n_generated,
                    "observation_tokens_per_step": w.n_observation, "prompt_tokens": w.n_prompt,
                    "decode_steps_per_step": w.n_decode_steps, "max_context": w.max_context,
-                   "scale": args.scale},
+                   "scale": args.scale, "shared_prefix_attention": bool(args.shared_prefix_attention)},
+        "measured_stream_read_GBs": round(stream_gbs, 1),
         "decode_only_tokens_per_s": round(n_gen / stats["decode_s"], 1) if stats["decode_s"] else None,
         "decode_step_hbm": {"achieved": round(stats["decode_bytes"] / stats["decode_s"] / 1e9, 1),
                             "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": round(stats["decode_bytes"] / stats["decode_s"] / 1e9 / HBM_PEAK_GBS, 4),
+                            "frac_of_measured_stream_read":
+                                round(stats["decode_bytes"] / stats["decode_s"] / 1e9 / stream_gbs, 4),
                             "note": "algorithmic bytes of all decode steps / wall time inside rl_decode_step"}
         if stats["decode_s"] else None,
         "recompute": {"tokens_per_s": round(stats["recompute_tokens"] / stats["recompute_s"], 1),

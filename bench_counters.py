@@ -31,7 +31,9 @@ def read_counter(path, counter):
         for r in csv.DictReader(f):
             if r["Counter_Name"] != counter:
                 continue
-            out[r["Kernel_Name"].split("(")[0]][int(r["Grid_Size"])].append(float(r["Counter_Value"]))
+            name = r["Kernel_Name"].split("(")[0]
+            name = name[5:] if name.startswith("void ") else name
+            out[name][int(r["Grid_Size"])].append(float(r["Counter_Value"]))
     return out
 
 
@@ -52,9 +54,52 @@ def trace_summary(path):
         print(f"| {g} | {n} | {t / n / 1e3:.2f} |")
 
 
+def decode_step_table(fetch_path, write_path):
+    """Per kernel and launch shape: mean HBM bytes fetched / written per dispatch (calibrated like
+    the attention summary), for every shape with at least 100 dispatches.  With the Qwen3-4B shape
+    and 128 trajectories the decode GEMM shapes are: QKV 240 workgroups (31.5 MB of weights), O and
+    down 160 workgroups each (21.0 and 49.8 MB; same launch shape, so they average to 35.4 MB),
+    gate-up 152 workgroups (99.6 MB), lm-head 1187 workgroups (777.9 MB)."""
+    fetch = read_counter(fetch_path, "FETCH_SIZE")
+    write = read_counter(write_path, "WRITE_SIZE")
+    copy_bytes = 151936 * 2560 * 2
+
+    def calib(tab):
+        best = max((max(v) for v in tab.get("__amd_rocclr_copyBuffer", {}).values()), default=None)
+        return copy_bytes / (best * 1024.0) if best else float("nan")
+
+    kf, kw = calib(fetch), calib(write)
+    expect = {("gemm_mfma_kernel<0, 2, 4>", 240 * 256): "QKV: 31.5 MB weights + 5 x 3.1 MB partial sums written",
+              ("gemm_mfma_kernel<0, 2, 4>", 160 * 256): "O / down mixed: 35.4 MB weights + 8 x 1.3 MB written",
+              ("gemm_mfma_kernel<2, 2, 4>", 152 * 256): "gate-up: 99.6 MB weights, 2.5 MB written",
+              ("gemm_mfma_kernel<0, 2, 4>", 1187 * 256): "lm-head: 777.9 MB weights, 77.8 MB logits written"}
+    print("# HBM traffic per dispatch of the decode-step kernels (Qwen3-4B shape, 128 trajectories)\n")
+    print("Commands (MI355X box, repository root; one counter per run; the rollout is shortened, the "
+          "decode launch shapes are those of the full workload):\n")
+    print("    rocprofv3 --pmc FETCH_SIZE --output-format csv -d out/pmc_fetch_all -o f -- python3 bench.py "
+          "--warmup 0 --no-cpu-baseline --scale 0.1")
+    print("    rocprofv3 --pmc WRITE_SIZE --output-format csv -d out/pmc_write_all -o w -- python3 bench.py "
+          "--warmup 0 --no-cpu-baseline --scale 0.1")
+    print("    python bench_counters.py --decode-step <f_counter_collection.csv> <w_counter_collection.csv>\n")
+    print(f"FETCH_SIZE factor {kf:.4f}, WRITE_SIZE factor {kw:.4f} (embedding-table copy of {copy_bytes} bytes).\n")
+    print("| kernel | grid (threads) | dispatches | fetched MB | written MB | algorithmic |\n|---|---|---|---|---|---|")
+    rows = []
+    for k, grids in fetch.items():
+        for g, vals in grids.items():
+            if len(vals) < 100:
+                continue
+            wv = write.get(k, {}).get(g, [])
+            rows.append((k, g, len(vals), sum(vals) / len(vals) * 1024 * kf / 1e6,
+                         sum(wv) / len(wv) * 1024 * kw / 1e6 if wv else float("nan")))
+    for k, g, n, fm, wm in sorted(rows, key=lambda r: -r[2] * (r[3] + r[4])):
+        print(f"| {k[:60]} | {g} | {n} | {fm:.2f} | {wm:.2f} | {expect.get((k, g), '')} |")
+
+
 def main():
     if sys.argv[1] == "--trace":
         return trace_summary(sys.argv[2])
+    if sys.argv[1] == "--decode-step":
+        return decode_step_table(sys.argv[2], sys.argv[3])
     fetch = read_counter(sys.argv[1], "FETCH_SIZE")
     write = read_counter(sys.argv[2], "WRITE_SIZE")
     vocab, hidden, n_traj, n_kv = 151936, 2560, 128, 8

@@ -66,6 +66,10 @@ typedef struct {
 
 #define RL_FLAG_GENERIC_KERNELS 1 /* bf16 models: use the shape-generic kernels even where the
                                      MFMA kernels apply (testing) */
+#define RL_FLAG_SHARED_PREFIX_ATTENTION 2 /* decode attention reads the pages that the members of a
+                                     forked group share (Section 2.3.2: several samples per prompt)
+                                     once per group of 16 / (n_q / n_kv) members instead of once per
+                                     member, and merges the result with each member's own pages */
 
 /*
  * Load a model: parse the blob (64-byte header: "RLW1", u32 version 1, the rl_model_config
@@ -159,6 +163,11 @@ int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches, double*
                    double* attn_kv_unique_bytes, int reset);
 /* GPU time of the timed decode steps, first kernel to sampler (HIP events), and their count. */
 int rl_timing_read_steps(rl_model* m, double* step_gpu_ms, int64_t* steps, int reset);
+
+/* Benchmark calibration: rate (GB/s) at which a plain kernel streams `bytes` (>= 16 MiB) of a
+ * freshly allocated device buffer, averaged over `iters` passes: the read ceiling of the GPU the
+ * library runs on, to set beside the nominal HBM figure.  Allocates and frees its own buffer. */
+int rl_measure_stream_read(size_t bytes, int32_t iters, double* gb_per_s);
 
 #ifdef __cplusplus
 }

@@ -5,4 +5,5 @@ library.  Importing this package does not load the library; the first use does, 
 fails loudly if the library has not been built (python paper_2509_06980_amd/build.py).
 """
 from .binding import (RolloutEngine, RolloutError, sample_from_logits, uniform_u32,  # noqa: F401
-                      load_library, LIB_PATH, EXPORTED_SYMBOLS)
+                      measure_stream_read, load_library, LIB_PATH, EXPORTED_SYMBOLS,
+                      FLAG_GENERIC_KERNELS, FLAG_SHARED_PREFIX_ATTENTION)

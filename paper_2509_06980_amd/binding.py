@@ -11,8 +11,12 @@ EXPORTED_SYMBOLS = [
     "rl_append_observation", "rl_decode_step", "rl_release", "rl_fork", "rl_traj_info",
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
     "rl_decode_step_forced", "rl_sample_from_logits", "rl_uniform_u32", "rl_timing_enable",
-    "rl_timing_read", "rl_timing_read_steps",
+    "rl_timing_read", "rl_timing_read_steps", "rl_measure_stream_read",
 ]
+
+
+FLAG_GENERIC_KERNELS = 1            # RL_FLAG_GENERIC_KERNELS
+FLAG_SHARED_PREFIX_ATTENTION = 2    # RL_FLAG_SHARED_PREFIX_ATTENTION
 
 
 class RolloutError(RuntimeError):
@@ -72,6 +76,7 @@ def load_library():
     lib.rl_timing_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int]
     lib.rl_timing_read_steps.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    lib.rl_measure_stream_read.argtypes = [C.c_size_t, C.c_int32, C.POINTER(C.c_double)]
     _lib = lib
     return lib
 
@@ -88,6 +93,13 @@ def _i32(a):
 
 def uniform_u32(seed, traj_id, position):
     return int(load_library().rl_uniform_u32(C.c_uint64(seed & (2**64 - 1)), int(traj_id), int(position)))
+
+
+def measure_stream_read(nbytes=1 << 31, iters=10):
+    """GB/s of a plain streaming-read kernel on this GPU (benchmark calibration)."""
+    out = C.c_double()
+    _check(load_library().rl_measure_stream_read(C.c_size_t(int(nbytes)), int(iters), C.byref(out)))
+    return out.value
 
 
 def sample_from_logits(logits, temperature, u32):

@@ -69,6 +69,7 @@ struct rl_model {
   int32_t* page_table = nullptr;
   // work buffers
   int Mcap = 0, Rl = 0, rows_per_item = 1;
+  bool cascade = false;    // shared-prefix decode attention
   float *h = nullptr, *qkv = nullptr, *ph = nullptr, *gu = nullptr, *logits = nullptr, *attn_scratch = nullptr;
   int pending_parts = 0;   // split-K partial sums of the last down-projection still to be added to h
   void *xa = nullptr, *xo = nullptr, *xm = nullptr, *qb = nullptr;
@@ -153,6 +154,7 @@ struct RowMeta {
   int n_items;
   const AttnMerge* merges;
   int n_merges;
+  const int32_t* rowlist;   // batch rows of the shared-prefix items
   bool prefill;      // multi-row items (append / recompute) instead of single decode rows
   double kv_bytes;   // keys + values the attention of one layer has to read
   bool time_attn;
@@ -224,7 +226,7 @@ void forward_mfma(rl_model* m, int M, const RowMeta& r) {
                                                 m->page_table, (bf16_t*)m->qb, m->pools[l], md, M);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
     launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, r.merges, r.n_merges,
-                          m->page_table, (bf16_t*)m->xo, m->attn_scratch, md, r.prefill);
+                          r.rowlist, m->page_table, (bf16_t*)m->xo, m->attn_scratch, md, r.prefill);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
     GemmPlan po = plan_gemm(M, H, qw, true);
     int so = launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->ph, M, H, qw, EPI_STORE,
@@ -275,24 +277,28 @@ void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done) {
 // ---- per-call metadata staging ----------------------------------------------------------------
 // Layout of the integer staging buffer for a pass over M rows:
 //   [0,M) tok  [M,2M) pos  [2M,3M) slot  [3M,4M) traj id  [4M,5M) index of the new token
-//   [5M,6M) forced / target ids  [6M, ...) attention items (8 ints each), then merge records (4)
+//   [5M,6M) forced / target ids  [6M, ...) attention items (8 ints each), merge records (8 ints
+//   each), then the row list of the shared-prefix items
 struct Staging {
   std::vector<int32_t> tok, pos, slot, traj, newpos, forced;
   std::vector<AttnItem> items;
   std::vector<AttnMerge> merges;
   std::vector<uint8_t> mask;
-  void clear() { tok.clear(); pos.clear(); slot.clear(); traj.clear(); newpos.clear(); forced.clear(); items.clear(); merges.clear(); mask.clear(); }
+  std::vector<int32_t> rowlist;
+  void clear() { tok.clear(); pos.clear(); slot.clear(); traj.clear(); newpos.clear(); forced.clear(); items.clear(); merges.clear(); mask.clear(); rowlist.clear(); }
 };
 
 struct DevMeta {
   int32_t *tok, *pos, *slot, *traj, *newpos, *forced;
   AttnItem* items;
   AttnMerge* merges;
+  int32_t* rowlist;
 };
 
 int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   size_t M = st.tok.size();
-  size_t need = 6 * M + 8 * st.items.size() + 4 * st.merges.size();
+  static_assert(sizeof(AttnItem) == 32 && sizeof(AttnMerge) == 32, "metadata records are 8 ints");
+  size_t need = 6 * M + 8 * st.items.size() + 8 * st.merges.size() + st.rowlist.size();
   if (need > m->meta_ints) return fail(RL_E_ARG, "internal: metadata staging too small");
   int32_t* h = m->h_meta;
   auto put = [&](const std::vector<int32_t>& v, size_t at) {
@@ -303,11 +309,13 @@ int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   if (!st.items.empty()) memcpy(h + 6 * M, st.items.data(), st.items.size() * sizeof(AttnItem));
   if (!st.merges.empty())
     memcpy(h + 6 * M + 8 * st.items.size(), st.merges.data(), st.merges.size() * sizeof(AttnMerge));
+  put(st.rowlist, 6 * M + 8 * st.items.size() + 8 * st.merges.size());
   HIPCHECK(hipMemcpyAsync(m->d_meta, h, need * 4, hipMemcpyHostToDevice, m->stream));
   dm->tok = m->d_meta; dm->pos = m->d_meta + M; dm->slot = m->d_meta + 2 * M;
   dm->traj = m->d_meta + 3 * M; dm->newpos = m->d_meta + 4 * M; dm->forced = m->d_meta + 5 * M;
   dm->items = (AttnItem*)(m->d_meta + 6 * M);
   dm->merges = (AttnMerge*)(m->d_meta + 6 * M + 8 * st.items.size());
+  dm->rowlist = m->d_meta + 6 * M + 8 * st.items.size() + 8 * st.merges.size();
   if (!st.mask.empty())
     HIPCHECK(hipMemcpyAsync(m->d_mask, st.mask.data(), st.mask.size(), hipMemcpyHostToDevice, m->stream));
   return RL_OK;
@@ -365,24 +373,80 @@ void add_items(rl_model* m, Staging& st, int row0, int cnt, int slot, int pos0) 
 // Decode items: one row per trajectory.  Contexts are cut into parts of about equal page count so
 // that ~kAttnTargetWgs workgroups share the keys / values evenly whatever the mix of lengths; a
 // part never gets fewer than 16 pages.
+// Shared-prefix ("cascade") mode: trajectories of the step whose leading pages are the same physical
+// pages (a forked group) get those pages read once per 16/G members by a gather item; each member
+// then covers only its own remainder and a merge record joins the two.
 const int kAttnTargetWgs = 1024;
-void add_decode_items(rl_model* m, Staging& st) {
+const int kMinSharedPages = 8;
+void add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {
   int n = (int)st.pos.size();
+  const int rpb = std::max(1, 16 / (m->md.nq / m->md.nkv));   // member rows per gather item
+  // own_lo[i]: first page the row reads by itself; shared part records per row
+  std::vector<int> own_lo(n, 0), sfirst(n, 0), snparts(n, 0), srow(n, 0);
+  struct Block { std::vector<int> rows; int pages; };
+  std::vector<Block> blocks;
+  if (m->cascade && m->mfma) {
+    std::unordered_map<int32_t, std::vector<int>> by_first;
+    for (int i = 0; i < n; i++)
+      if (!ts[i]->pages.empty() && m->refcount[ts[i]->pages[0]] > 1) by_first[ts[i]->pages[0]].push_back(i);
+    std::vector<int32_t> keys;
+    for (auto& kv : by_first) if (kv.second.size() >= 2) keys.push_back(kv.first);
+    std::sort(keys.begin(), keys.end());                 // deterministic order of the groups
+    for (int32_t k : keys) {
+      const std::vector<int>& rows = by_first[k];
+      const std::vector<int32_t>& p0 = ts[rows[0]]->pages;
+      int common = INT32_MAX;
+      for (int i : rows) {
+        const std::vector<int32_t>& pi = ts[i]->pages;
+        int lim = std::min({st.pos[i] / RL_PAGE, (int)pi.size(), (int)p0.size()});   // pages wholly before the row's position
+        int c = 0;
+        while (c < lim && pi[c] == p0[c]) c++;
+        common = std::min(common, c);
+      }
+      if (common < kMinSharedPages) continue;
+      for (size_t a = 0; a < rows.size(); a += rpb) {
+        Block b;
+        for (size_t j = a; j < std::min(rows.size(), a + rpb); j++) b.rows.push_back(rows[j]);
+        if (b.rows.size() < 2) continue;                 // a lone member reads its pages directly
+        b.pages = common;
+        for (int i : b.rows) own_lo[i] = common;
+        blocks.push_back(std::move(b));
+      }
+    }
+  }
   int64_t total_pages = 0;
-  for (int i = 0; i < n; i++) total_pages += st.pos[i] / RL_PAGE + 1;
+  for (int i = 0; i < n; i++) total_pages += st.pos[i] / RL_PAGE + 1 - own_lo[i];
+  for (auto& b : blocks) total_pages += b.pages;
   int chunk = (int)std::max<int64_t>(16, (total_pages * m->md.nkv + kAttnTargetWgs - 1) / kAttnTargetWgs);
   int next_part = 0;
+  for (auto& b : blocks) {
+    int parts = (b.pages + chunk - 1) / chunk;
+    int per = (b.pages + parts - 1) / parts;
+    int row0 = (int)st.rowlist.size();
+    for (size_t j = 0; j < b.rows.size(); j++) {
+      int i = b.rows[j];
+      st.rowlist.push_back(i);
+      sfirst[i] = next_part;
+      snparts[i] = parts;
+      srow[i] = (int)j;
+    }
+    for (int k = 0; k < parts; k++)
+      st.items.push_back(AttnItem{row0, (int)b.rows.size(), st.slot[b.rows[0]], 0, k * per,
+                                  std::min((k + 1) * per, b.pages), next_part++, 1});
+  }
   for (int i = 0; i < n; i++) {
     int np = st.pos[i] / RL_PAGE + 1;
-    int parts = m->mfma ? (np + chunk - 1) / chunk : 1;
-    if (parts <= 1) {
+    int own = np - own_lo[i];
+    int parts = m->mfma ? (own + chunk - 1) / chunk : 1;
+    if (parts <= 1 && snparts[i] == 0) {
       st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], 0, np, -1, 0});
       continue;
     }
-    int per = (np + parts - 1) / parts;
-    st.merges.push_back(AttnMerge{i, next_part, parts, 0});
+    int per = (own + parts - 1) / parts;
+    st.merges.push_back(AttnMerge{i, next_part, parts, sfirst[i], snparts[i], srow[i], 0, 0});
     for (int k = 0; k < parts; k++)
-      st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], k * per, std::min((k + 1) * per, np), next_part++, 0});
+      st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], own_lo[i] + k * per,
+                                  std::min(own_lo[i] + (k + 1) * per, np), next_part++, 0});
   }
 }
 
@@ -417,7 +481,7 @@ int prefill(rl_model* m, const std::vector<std::pair<Traj*, int>>& work) {
     DevMeta dm;
     int rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, true, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, dm.rowlist, true, 0.0, false};
     forward_rows(m, M, r);
     HIPCHECK(hipGetLastError());
     HIPCHECK(hipStreamSynchronize(m->stream));
@@ -474,7 +538,7 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
     max_pos = std::max(max_pos, nt - 1);
     kvb += (double)nt * 2.0 * m->md.nkv * m->md.d * m->el;
   }
-  add_decode_items(m, st);
+  add_decode_items(m, st, ts);
   DevMeta dm;
   rc = upload_meta(m, st, &dm);
   if (rc) return rc;
@@ -495,7 +559,8 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
       }
     }
   }
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), false, kvb, timed};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(),
+            dm.rowlist, false, kvb, timed};
   if (timed) (void)hipEventRecord(m->ev_step[0], m->stream);
   forward_rows(m, n, r);
   lm_head_rows(m, n, 0, n, false);
@@ -568,6 +633,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   m->bf16 = c.weight_dtype == 1;
   m->el = el;
   m->mfma = m->bf16 && mfma_shape_ok(c) && !(rt->flags & RL_FLAG_GENERIC_KERNELS);
+  m->cascade = (rt->flags & RL_FLAG_SHARED_PREFIX_ATTENTION) != 0;
   int max_pages = (rt->max_context + RL_PAGE - 1) / RL_PAGE;
   m->md = ModelDims{c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads, c.head_dim, c.intermediate,
                     c.vocab, c.rms_eps, c.qk_norm, max_pages};
@@ -674,7 +740,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc((void**)&m->logits, (size_t)m->Rl * V * 4));
   if (m->mfma)
     TRY(m->dalloc((void**)&m->attn_scratch,   // one slot per part of a cut decode row
-                  (size_t)(kAttnTargetWgs / c.n_kv_heads + 2 * rt->max_trajectories + 64) * c.n_kv_heads * 16 * 130 * 4));
+                  (size_t)(kAttnTargetWgs / c.n_kv_heads + 3 * rt->max_trajectories + 64) * c.n_kv_heads * 16 * 130 * 4));
   int nseg = sampler_nseg(V);
   TRY(m->dalloc((void**)&m->ss.segmax, (size_t)m->Rl * nseg * 4));
   TRY(m->dalloc((void**)&m->ss.segarg, (size_t)m->Rl * nseg * 4));
@@ -884,11 +950,12 @@ extern "C" int rl_debug_logits(rl_model* m, int32_t id, float* logits_out) {
   st.tok.push_back(t.tokens[nt - 1]);
   st.pos.push_back(nt - 1);
   st.slot.push_back(t.slot);
-  add_decode_items(m, st);
+  add_decode_items(m, st, std::vector<Traj*>{&t});
   DevMeta dm;
   int rc = upload_meta(m, st, &dm);
   if (rc) return rc;
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(), false, 0.0, false};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(),
+            dm.rowlist, false, 0.0, false};
   forward_rows(m, 1, r);   // rewrites the key / value of position nt-1 with the same values
   lm_head_rows(m, 1, 0, 1, false);
   HIPCHECK(hipGetLastError());
@@ -958,7 +1025,7 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
     DevMeta dm;
     rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, true, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, dm.rowlist, true, 0.0, false};
     forward_rows(m, M, r);
     if (m->mfma) {
       // fused pass: gather + final norm, lm-head with the log-softmax reduced in its epilogue (the
@@ -1037,6 +1104,54 @@ extern "C" int rl_timing_enable(rl_model* m, int32_t every) {
   if (!m || every < 0) return fail(RL_E_ARG, "bad argument");
   m->timing_every = every;
   return RL_OK;
+}
+
+// Plain streaming read for calibrating benchmarks: every thread keeps eight 16-byte loads in flight.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ p, size_t n,
+                                                          unsigned* __restrict__ sink) {
+  u32x4 a = {0u, 0u, 0u, 0u};
+  const size_t stride = (size_t)gridDim.x * 256 * 8;
+  for (size_t i = (size_t)blockIdx.x * 256 * 8 + threadIdx.x; i + 7 * 256 < n; i += stride) {
+    u32x4 x[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) x[u] = __builtin_nontemporal_load(p + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 8; u++) a ^= x[u];
+  }
+  if ((a[0] ^ a[1] ^ a[2] ^ a[3]) == 0x9e3779b9u) *sink = 1;   // keeps the loads alive
+}
+
+extern "C" int rl_measure_stream_read(size_t bytes, int32_t iters, double* gb_per_s) {
+  if (!gb_per_s || iters <= 0 || bytes < (1u << 24)) return fail(RL_E_ARG, "bad argument");
+  void* buf = nullptr;
+  unsigned* sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = RL_OK;
+  size_t n = bytes / 16 / (256 * 8) * (256 * 8);   // whole groups of 8 loads per workgroup
+  auto run = [&]() -> int {
+    HIPCHECK(hipMalloc(&buf, bytes));
+    HIPCHECK(hipMalloc((void**)&sink, 4));
+    HIPCHECK(hipMemset(buf, 1, bytes));
+    HIPCHECK(hipEventCreate(&e0));
+    HIPCHECK(hipEventCreate(&e1));
+    stream_read_kernel<<<512, 256>>>((const u32x4*)buf, n, sink);
+    HIPCHECK(hipDeviceSynchronize());
+    HIPCHECK(hipEventRecord(e0, nullptr));
+    for (int i = 0; i < iters; i++) stream_read_kernel<<<512, 256>>>((const u32x4*)buf, n, sink);
+    HIPCHECK(hipEventRecord(e1, nullptr));
+    HIPCHECK(hipEventSynchronize(e1));
+    HIPCHECK(hipGetLastError());
+    float ms = 0.f;
+    HIPCHECK(hipEventElapsedTime(&ms, e0, e1));
+    *gb_per_s = (double)n * 16.0 * iters / (ms * 1e-3) / 1e9;
+    return RL_OK;
+  };
+  rc = run();
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (buf) (void)hipFree(buf);
+  if (sink) (void)hipFree(sink);
+  return rc;
 }
 
 extern "C" int rl_timing_read_steps(rl_model* m, double* step_gpu_ms, int64_t* steps, int reset) {

@@ -5,23 +5,28 @@
 
 #include "rl_common.h"
 
-// One attention work item: up to 16 / (n_q / n_kv) consecutive batch rows of one trajectory and
-// a range of its pages.  Decode: one row; long contexts are cut into several items ("parts") so
-// that workgroups carry similar amounts of keys / values whatever the mix of context lengths.
-// Chunked prefill: several rows, always one part.
+// One attention work item: up to 16 / (n_q / n_kv) batch rows and a range of pages.  Decode: one
+// row; long contexts are cut into several items ("parts") so that workgroups carry similar amounts
+// of keys / values whatever the mix of context lengths.  Chunked prefill: several consecutive rows
+// of one trajectory, always one part.  Shared-prefix decode (gather = 1): the rows are members of a
+// group of trajectories whose first pages are the same physical pages (a forked prompt); the item
+// reads those pages once for all of them, every key visible to every row, and always leaves a
+// partial result that the merge step combines with each member's own remainder.
 struct AttnItem {
-  int32_t row0;    // first batch row
+  int32_t row0;    // first batch row; gather: index of the first entry in the row list
   int32_t nrows;   // rows in this item
   int32_t slot;    // trajectory slot (row of the page table)
   int32_t pos0;    // position of row0; row r sits at pos0 + r and sees positions <= pos0 + r
   int32_t pg_lo;   // pages [pg_lo, pg_hi) of the trajectory are this item's share
   int32_t pg_hi;
   int32_t part;    // >= 0: partial result goes to scratch slot `part`; -1: the item is complete
-  int32_t pad;
+  int32_t gather;  // 1: batch rows are rowlist[row0 + r] (shared-prefix item)
 };
-// Rows whose attention was cut into parts: merge scratch slots [first, first + nparts).
+// Rows whose attention was cut into parts: merge, in this order, the shared-prefix parts (scratch
+// slots [sfirst, sfirst + snparts), where the row is row `sr` of the item) and the row's own parts
+// (slots [first, first + nparts), row 0 of the item).
 struct AttnMerge {
-  int32_t row, first, nparts, pad;
+  int32_t row, first, nparts, sfirst, snparts, sr, pad0, pad1;
 };
 
 struct KvPool {      // one layer
@@ -104,8 +109,8 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 #endif
 void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
                            int n_items, const AttnMerge* merges, int n_merges,
-                           const int32_t* page_table, bf16_t* o, float* scratch,
-                           const ModelDims& md, bool prefill);
+                           const int32_t* rowlist, const int32_t* page_table, bf16_t* o,
+                           float* scratch, const ModelDims& md, bool prefill);
 
 // ---- sampler ---------------------------------------------------------------------------------
 struct SamplerScratch {

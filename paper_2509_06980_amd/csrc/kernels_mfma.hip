@@ -368,9 +368,9 @@ __device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
 
 __global__ __launch_bounds__(256) void attention_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kpool, const bf16_t* __restrict__ vpool,
-    const AttnItem* __restrict__ items, const int32_t* __restrict__ page_table,
-    bf16_t* __restrict__ o, float* __restrict__ scratch, int nq, int nkv, int gshift,
-    int pt_stride, float scale2) {
+    const AttnItem* __restrict__ items, const int32_t* __restrict__ rowlist,
+    const int32_t* __restrict__ page_table, bf16_t* __restrict__ o, float* __restrict__ scratch,
+    int nq, int nkv, int gshift, int pt_stride, float scale2) {
   __shared__ float s_acc[4 * 16 * 128];
   __shared__ float s_m[4 * 16];
   __shared__ float s_l[4 * 16];
@@ -383,7 +383,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, n = lane & 15, r = n >> gshift, hq = n & ((1 << gshift) - 1);
   const bool colvalid = r < it.nrows;
-  const int mypos = it.pos0 + r;
+  // shared-prefix items: every page of the range lies before every member's position
+  const int mypos = it.gather ? 0x3fffffff : it.pos0 + r;
+  const int qrow = !colvalid ? 0 : (it.gather ? rowlist[it.row0 + r] : it.row0 + r);
   const int per = (it.pg_hi - it.pg_lo + 3) >> 2;
   const int pg0 = it.pg_lo + wave * per, pg1 = min(pg0 + per, it.pg_hi);
   const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
@@ -393,7 +395,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   for (int c = 0; c < 4; c++) {
     qreg[c] = (u32x4){0u, 0u, 0u, 0u};
     if (colvalid)
-      qreg[c] = *(const u32x4*)(q + ((size_t)(it.row0 + r) * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
+      qreg[c] = *(const u32x4*)(q + ((size_t)qrow * nq + ((kvh << gshift) + hq)) * 128 + c * 32 + g * 8);
   }
   f32x4 acc[8];
 #pragma unroll
@@ -591,35 +593,57 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
   }
 }
 
-// grid (n_merges, nkv), block 256: merge the parts of one (row, kv head) in ascending order
+// grid (n_merges, nkv), block 256: merge the parts of one (row, kv head) in a fixed order: the
+// shared-prefix parts first (the row is row `sr` of those items), then the row's own parts.
 __global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ scratch,
                                                               const AttnMerge* __restrict__ merges,
                                                               bf16_t* __restrict__ o, int nq,
                                                               int nkv, int gshift) {
   const AttnMerge mg = merges[blockIdx.x];
   const int kvh = blockIdx.y, tid = threadIdx.x;
-  const float* src = scratch + ((size_t)mg.first * nkv + kvh) * (16 * 130);
   const size_t stride = (size_t)nkv * (16 * 130);
   const int cn = tid >> 4, d0 = (tid & 15) * 8;
-  float mt, L, o8[8];
-  attn_merge_store(src + 16 * 128, src + 16 * 128 + 16, src, mg.nparts, stride, stride, cn, d0, &mt,
-                   &L, o8);
-  const int cr = cn >> gshift, chq = cn & ((1 << gshift) - 1);
-  if (cr == 0) {   // cut rows are decode rows: one query row per item
-    float inv = 1.0f / L;
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; e++)
-      w[e] = (uint32_t)f2bf(o8[2 * e] * inv) | ((uint32_t)f2bf(o8[2 * e + 1] * inv) << 16);
-    *(uint4*)(o + atile_off(mg.row, ((kvh << gshift) + chq) * 128 + d0, nq * 128)) =
-        make_uint4(w[0], w[1], w[2], w[3]);
+  if ((cn >> gshift) != 0) return;   // decode rows: one query row, columns 0 .. G-1
+  const int total = mg.snparts + mg.nparts;
+  const int scol = (mg.sr << gshift) + cn;
+  // part w: slot and column holding this row's head cn
+  auto src_of = [&](int w, int* col) -> const float* {
+    const bool sh = w < mg.snparts;
+    *col = sh ? scol : cn;
+    const int slot = sh ? mg.sfirst + w : mg.first + (w - mg.snparts);
+    return scratch + ((size_t)slot * nkv + kvh) * (16 * 130);
+  };
+  float mt = ATT_NEG;
+  for (int w = 0; w < total; w++) {
+    int col;
+    const float* src = src_of(w, &col);
+    mt = fmaxf(mt, src[16 * 128 + col]);
   }
+  float L = 0.f, o8[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) o8[e] = 0.f;
+  for (int w = 0; w < total; w++) {
+    int col;
+    const float* src = src_of(w, &col);
+    const float f = exp2f(src[16 * 128 + col] - mt);
+    L += f * src[16 * 128 + 16 + col];
+    const float* a = src + (size_t)col * 128 + d0;
+#pragma unroll
+    for (int e = 0; e < 8; e++) o8[e] += f * a[e];
+  }
+  const float inv = 1.0f / L;
+  uint32_t wv[4];
+#pragma unroll
+  for (int e = 0; e < 4; e++)
+    wv[e] = (uint32_t)f2bf(o8[2 * e] * inv) | ((uint32_t)f2bf(o8[2 * e + 1] * inv) << 16);
+  *(uint4*)(o + atile_off(mg.row, ((kvh << gshift) + cn) * 128 + d0, nq * 128)) =
+      make_uint4(wv[0], wv[1], wv[2], wv[3]);
 }
 
 void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const AttnItem* items,
                            int n_items, const AttnMerge* merges, int n_merges,
-                           const int32_t* page_table, bf16_t* o, float* scratch,
-                           const ModelDims& md, bool prefill) {
+                           const int32_t* rowlist, const int32_t* page_table, bf16_t* o,
+                           float* scratch, const ModelDims& md, bool prefill) {
   if (n_items <= 0) return;
   float scale2 = 1.4426950408889634f / sqrtf((float)md.d);
   int gshift = 0;
@@ -631,8 +655,8 @@ void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const At
     return;
   }
   attention_mfma_kernel<<<n_items * md.nkv, 256, 0, s>>>(q, (const bf16_t*)pool.k,
-                                                        (const bf16_t*)pool.v, items, page_table, o,
-                                                        scratch, md.nq, md.nkv, gshift,
+                                                        (const bf16_t*)pool.v, items, rowlist,
+                                                        page_table, o, scratch, md.nq, md.nkv, gshift,
                                                         md.max_pages_per_traj, scale2);
   if (n_merges > 0)
     attention_merge_kernel<<<dim3(n_merges, md.nkv), 256, 0, s>>>(scratch, merges, o, md.nq, md.nkv,

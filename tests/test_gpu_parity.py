@@ -107,6 +107,38 @@ def test_bf16_lockstep(name, flags):
     assert np.all(rec[m == 1] == 0.0)
 
 
+@pytest.mark.parametrize("name,group,prompt", [("small-d128", 5, 200), ("small-g2", 3, 150),
+                                               ("small-g1", 4, 133), ("small-g8", 5, 300)])
+def test_shared_prefix_decode_attention(name, group, prompt):
+    # forked groups whose shared prompt spans many pages: with the shared-prefix flag the decode
+    # attention reads those pages once per block of 16/G members (blocks of several members, a lone
+    # member, a prefix long enough to be cut into parts) and merges with each member's own pages
+    shape = SHAPES[name]
+    blob = make_weight_blob(shape, seed=5, weight_std=0.03, gain_std=0.1)
+    w = uniform_turns("shared", shape.vocab, 2 * group, prompt, 2, 6, 19, 1.0, group_size=group,
+                      final_release=False)
+    kw = dict(max_context=512, max_trajectories=16, kv_pool_pages=400)
+    o = OracleEngine(blob, **kw)
+    g = rl.RolloutEngine(blob, flags=rl.FLAG_SHARED_PREFIX_ATTENTION, **kw)
+    r = run_lockstep(o, g, w, check_logits_every=2, logit_rows=2 * group)
+    print(name, r)
+    assert r["max_logp_err"] < TOL_BF16 and r["max_logit_err"] < TOL_BF16, r
+    # same calls without the flag: same integer state, log-probs within the bf16 tolerance
+    p = rl.RolloutEngine(blob, **kw)
+    for ev in w.events:
+        if ev[0] == "append":
+            p.append_observation(ev[1], ev[2], ev[3])
+        elif ev[0] == "fork":
+            p.fork(ev[1], ev[2])
+        elif ev[0] == "decode":
+            p.decode_step_forced(ev[1], ev[2], np.array([g.traj_read(int(t))[0][p.traj_info(int(t))[0]]
+                                                         for t in ev[1]], np.int32))
+    for t in range(2 * group):
+        a, b = g.traj_read(t), p.traj_read(t)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[3], b[3])
+        assert np.abs(a[2] - b[2]).max() < TOL_BF16
+
+
 def test_mfma_long_context_split_attention_and_chunked_prefill():
     # context long enough that decode attention is split over several workgroups, appended with a
     # row budget that forces several prefill passes and splits a trajectory across passes
