@@ -40,6 +40,7 @@ struct Traj {
   std::vector<uint8_t> mask;
   std::vector<float> logp;
   std::vector<int32_t> pages;
+  int shared_lead = 0;  // leading pages that were shared with another trajectory by a fork
 };
 
 struct LayerW {
@@ -432,21 +433,21 @@ void add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {
     }
     for (int k = 0; k < parts; k++)
       st.items.push_back(AttnItem{row0, (int)b.rows.size(), st.slot[b.rows[0]], 0, k * per,
-                                  std::min((k + 1) * per, b.pages), next_part++, 1});
+                                  std::min((k + 1) * per, b.pages), next_part++, (b.pages << 8) | 1});
   }
   for (int i = 0; i < n; i++) {
     int np = st.pos[i] / RL_PAGE + 1;
     int own = np - own_lo[i];
     int parts = m->mfma ? (own + chunk - 1) / chunk : 1;
     if (parts <= 1 && snparts[i] == 0) {
-      st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], 0, np, -1, 0});
+      st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], 0, np, -1, ts[i]->shared_lead << 8});
       continue;
     }
     int per = (own + parts - 1) / parts;
     st.merges.push_back(AttnMerge{i, next_part, parts, sfirst[i], snparts[i], srow[i], 0, 0});
     for (int k = 0; k < parts; k++)
       st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], own_lo[i] + k * per,
-                                  std::min(own_lo[i] + (k + 1) * per, np), next_part++, 0});
+                                  std::min(own_lo[i] + (k + 1) * per, np), next_part++, ts[i]->shared_lead << 8});
   }
 }
 
@@ -892,6 +893,7 @@ extern "C" int rl_fork(rl_model* m, int32_t src, const int32_t* dst_ids, int32_t
     t.slot = m->free_slots.back();
     m->free_slots.pop_back();
     for (int k = 0; k < n_shared; k++) m->refcount[t.pages[k]]++;
+    t.shared_lead = std::max(t.shared_lead, n_shared);
     for (int k = n_shared; k < n_shared + n_own; k++) {
       int p = take_page(m);
       pairs.push_back(t.pages[k]);
@@ -900,6 +902,10 @@ extern "C" int rl_fork(rl_model* m, int32_t src, const int32_t* dst_ids, int32_t
     }
     for (size_t k = 0; k < t.pages.size(); k++) upd.insert(upd.end(), {t.slot, (int32_t)k, t.pages[k]});
     m->traj[dst_ids[i]] = std::move(t);
+  }
+  if (n > 0) {
+    Traj& st = m->traj.find(src)->second;
+    st.shared_lead = std::max(st.shared_lead, n_shared);
   }
   if (!upd.empty()) { rc = push_page_updates(m, upd); if (rc) return rc; }
   size_t np = pairs.size() / 2, done = 0, cap = m->meta_ints / 2;

@@ -20,7 +20,9 @@ struct AttnItem {
   int32_t pg_lo;   // pages [pg_lo, pg_hi) of the trajectory are this item's share
   int32_t pg_hi;
   int32_t part;    // >= 0: partial result goes to scratch slot `part`; -1: the item is complete
-  int32_t gather;  // 1: batch rows are rowlist[row0 + r] (shared-prefix item)
+  int32_t gather;  // bit 0: batch rows are rowlist[row0 + r] (shared-prefix item); bits 8..: number
+                   // of leading pages of the trajectory that other trajectories share (decode: read
+                   // with plain, cached loads; the rest is streamed)
 };
 // Rows whose attention was cut into parts: merge, in this order, the shared-prefix parts (scratch
 // slots [sfirst, sfirst + snparts), where the row is row `sr` of the item) and the row's own parts

@@ -274,12 +274,26 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
 #define ATT_NEG (-1.0e30f)
 
 // One page of the online-softmax loop; see the kernels below for the variables they use.
-#define ATT_LOAD(KR, VR, PAGEID)                                              \
+// Two flavours of the page load.  The decode kernel reads a trajectory's own pages once per step:
+// those loads carry the non-temporal hint (measured 8-10 % more bandwidth than plain loads).  Pages
+// shared with other trajectories of the step (a forked prompt) keep plain loads so that the group
+// finds them in L2, and so does the prefill kernel, which re-reads pages across waves and items.
+// The choice is made per wave, outside the page loop: inside it the compiler would merge the two
+// loads into one and drop the hint.
+#define ATT_LOAD_PLAIN(KR, VR, PAGEID)                                        \
   {                                                                           \
     const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
     _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
       KR[c] = *(const u32x4*)(kpool + base_ + c * 512);                       \
       VR[c] = *(const u32x4*)(vpool + base_ + c * 512);                       \
+    }                                                                         \
+  }
+#define ATT_LOAD_STREAM(KR, VR, PAGEID)                                       \
+  {                                                                           \
+    const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
+    _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
+      KR[c] = __builtin_nontemporal_load((const u32x4*)(kpool + base_ + c * 512)); \
+      VR[c] = __builtin_nontemporal_load((const u32x4*)(vpool + base_ + c * 512)); \
     }                                                                         \
   }
 #define ATT_PAGE(KR, VR, PG)                                                  \
@@ -320,24 +334,24 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
       acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0); \
     }                                                                         \
   }
-// The page loop shared by the decode and the prefill kernel (uses pt, pg0, pg1, pglast, head_off,
-// kpool, vpool, nkv and the buffers kA, vA, kB, vB of the enclosing kernel).
-#define ATT_PAGE_LOOP                                                         \
+// The decode kernel's page loop (uses pt, pg0, pg1, pglast, head_off, kpool, vpool, nkv and the
+// buffers kA, vA, kB, vB of the enclosing kernel); LOAD is one of the two load macros.
+#define ATT_PAGE_LOOP(LOAD)                                                   \
   if (pg0 < pg1) {                                                            \
     int id_cur = pt[pg0];                                                     \
     int id_nxt = pt[min(pg0 + 1, pglast)];                                    \
-    ATT_LOAD(kA, vA, id_cur)                                                  \
+    LOAD(kA, vA, id_cur)                                                      \
     for (int pg = pg0; pg < pg1; pg += 2) {                                   \
       /* page pg is in A; request the table entry of pg+2 (first: the counter of outstanding \
          loads is in order, and its consumer must not wait for the page behind it), then pg+1 -> B */ \
       int id_n2 = pt[min(pg + 2, pglast)];                                    \
-      ATT_LOAD(kB, vB, id_nxt)                                                \
+      LOAD(kB, vB, id_nxt)                                                    \
       __builtin_amdgcn_sched_barrier(0);                                      \
       ATT_PAGE(kA, vA, pg)                                                    \
       __builtin_amdgcn_sched_barrier(0);                                      \
       /* page pg+1 is in B; request the table entry of pg+3, then pg+2 -> A */ \
       id_nxt = pt[min(pg + 3, pglast)];                                       \
-      ATT_LOAD(kA, vA, id_n2)                                                 \
+      LOAD(kA, vA, id_n2)                                                     \
       __builtin_amdgcn_sched_barrier(0);                                      \
       ATT_PAGE(kB, vB, pg + 1)                                                \
       __builtin_amdgcn_sched_barrier(0);                                      \
@@ -384,8 +398,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   const int g = lane >> 4, n = lane & 15, r = n >> gshift, hq = n & ((1 << gshift) - 1);
   const bool colvalid = r < it.nrows;
   // shared-prefix items: every page of the range lies before every member's position
-  const int mypos = it.gather ? 0x3fffffff : it.pos0 + r;
-  const int qrow = !colvalid ? 0 : (it.gather ? rowlist[it.row0 + r] : it.row0 + r);
+  const bool gather = (it.gather & 1) != 0;
+  const int mypos = gather ? 0x3fffffff : it.pos0 + r;
+  const int qrow = !colvalid ? 0 : (gather ? rowlist[it.row0 + r] : it.row0 + r);
   const int per = (it.pg_hi - it.pg_lo + 3) >> 2;
   const int pg0 = it.pg_lo + wave * per, pg1 = min(pg0 + per, it.pg_hi);
   const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
@@ -410,7 +425,12 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   const int pglast = max(pg1 - 1, pg0);
   const size_t head_off = (size_t)kvh * 2048 + lane * 8;
   u32x4 kA[4], vA[4], kB[4], vB[4];
-  ATT_PAGE_LOOP
+  // a wave whose share of the pages starts behind the trajectory's shared leading pages streams
+  if (pg0 >= (it.gather >> 8)) {
+    ATT_PAGE_LOOP(ATT_LOAD_STREAM)
+  } else {
+    ATT_PAGE_LOOP(ATT_LOAD_PLAIN)
+  }
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
   // wave partials -> LDS: acc[jb][i] is O^T[d = 16 jb + 4 g + i][column n]
@@ -558,15 +578,15 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
   if (pg0 < pg1) {
     int id_cur = pt[pg0];
     int id_nxt = pt[min(pg0 + 1, pglast)];
-    ATT_LOAD(kA, vA, id_cur)
+    ATT_LOAD_PLAIN(kA, vA, id_cur)
     for (int pg = pg0; pg < pg1; pg += 2) {
       int id_n2 = pt[min(pg + 2, pglast)];
-      ATT_LOAD(kB, vB, id_nxt)
+      ATT_LOAD_PLAIN(kB, vB, id_nxt)
       __builtin_amdgcn_sched_barrier(0);
       PF_PAGE(kA, vA, pg)
       __builtin_amdgcn_sched_barrier(0);
       id_nxt = pt[min(pg + 3, pglast)];
-      ATT_LOAD(kA, vA, id_n2)
+      ATT_LOAD_PLAIN(kA, vA, id_n2)
       __builtin_amdgcn_sched_barrier(0);
       PF_PAGE(kB, vB, pg + 1)
       __builtin_amdgcn_sched_barrier(0);
