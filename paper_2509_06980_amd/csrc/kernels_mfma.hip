@@ -184,7 +184,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
           ((bf16_t*)Cv)[atile_off(row, j, N >> 1)] = f2bf(y);
         }
       } else if (row < M) {
-        Cp[(size_t)row * N + col] = v;
+        __builtin_nontemporal_store(v, &Cp[(size_t)row * N + col]);   // leaves the L2 early instead of at the end of the kernel
       }
     }
   }
