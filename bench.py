@@ -51,14 +51,25 @@ def recorded_traffic(config):
     return None
 
 
-def run_rollout(engine, w, shape, stats):
-    """Replay the workload once (free-running sampling); returns generated token count."""
+def run_rollout(engine, w, shape, stats, fuse_appends=False):
+    """Replay the workload once (free-running sampling); returns generated token count.
+    fuse_appends: an append event directly followed by a decode event is issued as one call
+    (rl_decode_step_with_appends); its time is booked under the decode step."""
     kvtok = shape.kv_bytes_per_token()
     wbytes = shape.decode_weight_bytes()
     ctx = {}
     n_gen = 0
-    for ev in w.events:
+    pending_append = None
+    events = w.events
+    for k, ev in enumerate(events):
         kind = ev[0]
+        if fuse_appends and kind == "append" and k + 1 < len(events) and events[k + 1][0] == "decode":
+            pending_append = ev
+            stats["append_rows"] = stats.get("append_rows", 0) + int(np.sum(ev[3]))
+            for i, c in zip(ev[1], ev[3]):
+                ctx[int(i)] = ctx.get(int(i), 0) + int(c)
+            stats["fused_appends"] = stats.get("fused_appends", 0) + 1
+            continue
         if kind != "decode" and stats.get("turns"):
             stats["turns"][-1]["closed"] = True
         if kind == "append":
@@ -80,7 +91,12 @@ def run_rollout(engine, w, shape, stats):
                 ctx[int(d)] = ctx[int(ev[1])]
         elif kind == "decode":
             t0 = time.perf_counter()
-            engine.decode_step(ev[1], ev[2], ev[3])
+            if pending_append is not None:
+                engine.decode_step_with_appends(pending_append[1], pending_append[2], pending_append[3],
+                                                ev[1], ev[2], ev[3])
+                pending_append = None
+            else:
+                engine.decode_step(ev[1], ev[2], ev[3])
             dt = time.perf_counter() - t0
             stats["decode_s"] += dt
             tot = 0
@@ -153,16 +169,19 @@ def tool_loop_bench(rl, blob, shape, args):
     plans = [TrajectoryPlan(i, p, t) for i, p, t in raw]
     res = {"plans": "128 trajectories, prompt 512, turns U{1..6}, gen U{32..512}, obs U{64..1024} (x scale), "
                     "tool latency U%s ms on worker threads" % (tuple(args.tool_latency_ms),)}
-    for policy in ("continuous", "lockstep"):
+    for name, policy, fuse in (("continuous", "continuous", True), ("continuous_separate_appends", "continuous", False),
+                               ("lockstep", "lockstep", False)):
         eng = rl.RolloutEngine(blob, max_context=longest + 16, max_trajectories=128,
                                kv_pool_pages=128 * (longest // 16 + 2) + 64)
         tools = MockTools(shape.vocab, seed=5, latency=tuple(args.tool_latency_ms), clock="wall", workers=32)
-        _, st = ToolLoop(eng, plans, tools, temperature=1.0, rng_seed=3).run(policy)
+        _, st = ToolLoop(eng, plans, tools, temperature=1.0, rng_seed=3, fuse=fuse).run(policy)
         tools.close()
         eng.close()
+        policy = name
         res[policy] = {"tokens_per_s": round(st["generated"] / st["wall_s"], 1),
                        "wall_s": round(st["wall_s"], 2), "decode_steps": st["decode_steps"],
                        "mean_batch": round(st["mean_batch"], 1), "append_calls": st["append_calls"],
+                       "fused_steps": st.get("fused_steps", 0),
                        "gpu_idle_wait_s": round(st["wait_s"], 2), "decode_s": round(st["decode_s"], 2),
                        "append_s": round(st["append_s"], 2)}
         print(f"[bench] tool loop {policy}: {res[policy]}", file=sys.stderr, flush=True)
@@ -208,6 +227,8 @@ def main():
     ap.add_argument("--timing-every", type=int, default=16)
     ap.add_argument("--shared-prefix-attention", action="store_true",
                     help="decode attention reads a forked group's shared pages once per block of members")
+    ap.add_argument("--fuse-appends", action="store_true",
+                    help="issue an append that is directly followed by a decode step as one call")
     ap.add_argument("--tool-loop", action="store_true",
                     help="also run the ragged 128-trajectory mix against the mock tool layer (wall-clock "
                          "latencies), continuous batching vs. the turn-barrier baseline")
@@ -242,7 +263,8 @@ def main():
 
     for i in range(args.warmup):
         t0 = time.perf_counter()
-        run_rollout(eng, w, shape, dict(append_s=0.0, decode_s=0.0, decode_bytes=0.0, decode_steps=0))
+        run_rollout(eng, w, shape, dict(append_s=0.0, decode_s=0.0, decode_bytes=0.0, decode_steps=0),
+                    args.fuse_appends)
         print(f"[bench] warmup {i}: {time.perf_counter() - t0:.2f}s", file=sys.stderr, flush=True)
 
     eng.timing_enable(args.timing_every)
@@ -252,7 +274,7 @@ def main():
     t0 = time.perf_counter()
     n_gen = 0
     for i in range(args.steps):
-        n_gen += run_rollout(eng, w, shape, stats)
+        n_gen += run_rollout(eng, w, shape, stats, args.fuse_appends)
         print(f"[bench] step {i}: {time.perf_counter() - t0:.2f}s elapsed", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -286,7 +308,8 @@ def main():
                    "trajectories": w.n_trajectories, "generated_tokens_per_step": w.n_generated,
                    "observation_tokens_per_step": w.n_observation, "prompt_tokens": w.n_prompt,
                    "decode_steps_per_step": w.n_decode_steps, "max_context": w.max_context,
-                   "scale": args.scale, "shared_prefix_attention": bool(args.shared_prefix_attention)},
+                   "scale": args.scale, "shared_prefix_attention": bool(args.shared_prefix_attention),
+                   "fuse_appends": bool(args.fuse_appends)},
         "measured_stream_read_GBs": round(stream_gbs, 1),
         "decode_only_tokens_per_s": round(n_gen / stats["decode_s"], 1) if stats["decode_s"] else None,
         "decode_step_hbm": {"achieved": round(stats["decode_bytes"] / stats["decode_s"] / 1e9, 1),

@@ -108,6 +108,22 @@ int rl_append_observation(rl_model* m, const int32_t* traj_ids, int32_t n,
 int rl_decode_step(rl_model* m, const int32_t* active_traj_ids, int32_t n, float temperature,
                    uint64_t rng_seed, int32_t* token_ids_out, float* logprobs_out);
 
+/*
+ * Update + Generate in one pass (continuous batching, Section 2.3.2: tool calls return at different
+ * times, the batch must not wait): exactly rl_append_observation(app_*) followed by
+ * rl_decode_step(active_traj_ids, ...), but the appended tokens' keys / values are computed in the
+ * same forward pass as the decode rows, so the weights are streamed once for both.  A trajectory
+ * may be in both lists (it decodes right after its observation).  If the appended rows and the
+ * decode rows exceed one pass (max_batch_rows) the append is prefilled first.  Results equal the
+ * two separate calls within floating-point tolerance (integer state identically).  Errors: those
+ * of the two calls; when the append part succeeds and the decode part is rejected, the append has
+ * taken effect (as it would have with two calls).
+ */
+int rl_decode_step_with_appends(rl_model* m, const int32_t* app_traj_ids, int32_t n_app,
+                                const int32_t* app_tokens, const int32_t* app_lens,
+                                const int32_t* active_traj_ids, int32_t n, float temperature,
+                                uint64_t rng_seed, int32_t* token_ids_out, float* logprobs_out);
+
 /* Trajectory ended: give its pages back (shared pages when their last holder lets go). */
 int rl_release(rl_model* m, const int32_t* traj_ids, int32_t n);
 
@@ -143,6 +159,11 @@ int rl_recompute_logprobs(rl_model* m, const int32_t* traj_ids, int32_t n, float
 int rl_debug_logits(rl_model* m, int32_t traj_id, float* logits_out);
 int rl_decode_step_forced(rl_model* m, const int32_t* traj_ids, int32_t n, float temperature,
                           const int32_t* forced_token_ids, float* logprobs_out);
+/* rl_decode_step_with_appends with forced tokens (parity aid). */
+int rl_decode_step_forced_with_appends(rl_model* m, const int32_t* app_traj_ids, int32_t n_app,
+                                       const int32_t* app_tokens, const int32_t* app_lens,
+                                       const int32_t* traj_ids, int32_t n, float temperature,
+                                       const int32_t* forced_token_ids, float* logprobs_out);
 
 /* The sampler in isolation, on the GPU: `rows` rows of `vocab` float32 logits (host), one
  * uniform per row.  Same arithmetic as inside rl_decode_step. */

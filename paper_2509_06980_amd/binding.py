@@ -12,6 +12,7 @@ EXPORTED_SYMBOLS = [
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
     "rl_decode_step_forced", "rl_sample_from_logits", "rl_uniform_u32", "rl_timing_enable",
     "rl_timing_read", "rl_timing_read_steps", "rl_measure_stream_read",
+    "rl_decode_step_with_appends", "rl_decode_step_forced_with_appends",
 ]
 
 
@@ -61,6 +62,10 @@ def load_library():
     lib.rl_append_observation.argtypes = [C.c_void_p, _I32P, C.c_int32, _I32P, _I32P]
     lib.rl_decode_step.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_float, C.c_uint64, _I32P, _F32P]
     lib.rl_decode_step_forced.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_float, _I32P, _F32P]
+    lib.rl_decode_step_with_appends.argtypes = [C.c_void_p, _I32P, C.c_int32, _I32P, _I32P, _I32P, C.c_int32,
+                                                C.c_float, C.c_uint64, _I32P, _F32P]
+    lib.rl_decode_step_forced_with_appends.argtypes = [C.c_void_p, _I32P, C.c_int32, _I32P, _I32P, _I32P,
+                                                       C.c_int32, C.c_float, _I32P, _F32P]
     lib.rl_release.argtypes = [C.c_void_p, _I32P, C.c_int32]
     lib.rl_fork.argtypes = [C.c_void_p, C.c_int32, _I32P, C.c_int32]
     lib.rl_traj_info.argtypes = [C.c_void_p, C.c_int32, _I32P, _I32P]
@@ -170,6 +175,38 @@ class RolloutEngine:
         lps = np.empty(ids.size, np.float32)
         _check(self._lib.rl_decode_step_forced(self._h, pi, ids.size, float(temperature), pf,
                                                lps.ctypes.data_as(_F32P)))
+        return lps
+
+    def decode_step_with_appends(self, app_ids, app_tokens, app_lens, traj_ids, temperature, rng_seed):
+        """append_observation(app_*) followed by decode_step(traj_ids, ...) in one forward pass."""
+        aids, pa = _i32(app_ids)
+        toks, pt = _i32(app_tokens)
+        ls, pl = _i32(app_lens)
+        if ls.size != aids.size or toks.size != int(ls.sum()):
+            raise RolloutError(-1, "lens / ids / tokens mismatch")
+        ids, pi = _i32(traj_ids)
+        out = np.empty(ids.size, np.int32)
+        lps = np.empty(ids.size, np.float32)
+        _check(self._lib.rl_decode_step_with_appends(
+            self._h, pa, aids.size, pt, pl, pi, ids.size, float(temperature),
+            C.c_uint64(int(rng_seed) & (2**64 - 1)), out.ctypes.data_as(_I32P), lps.ctypes.data_as(_F32P)))
+        return out, lps
+
+    def decode_step_forced_with_appends(self, app_ids, app_tokens, app_lens, traj_ids, temperature,
+                                        forced_token_ids):
+        aids, pa = _i32(app_ids)
+        toks, pt = _i32(app_tokens)
+        ls, pl = _i32(app_lens)
+        if ls.size != aids.size or toks.size != int(ls.sum()):
+            raise RolloutError(-1, "lens / ids / tokens mismatch")
+        ids, pi = _i32(traj_ids)
+        fz, pf = _i32(forced_token_ids)
+        if fz.size != ids.size:
+            raise RolloutError(-1, "forced ids / traj ids mismatch")
+        lps = np.empty(ids.size, np.float32)
+        _check(self._lib.rl_decode_step_forced_with_appends(
+            self._h, pa, aids.size, pt, pl, pi, ids.size, float(temperature), pf,
+            lps.ctypes.data_as(_F32P)))
         return lps
 
     def release(self, traj_ids):

@@ -70,6 +70,7 @@ struct rl_model {
   int32_t* page_table = nullptr;
   // work buffers
   int Mcap = 0, Rl = 0, rows_per_item = 1;
+  size_t part_rows = 0;    // rows of the split-K partial-sum buffers qkv and ph
   bool cascade = false;    // shared-prefix decode attention
   float *h = nullptr, *qkv = nullptr, *ph = nullptr, *gu = nullptr, *logits = nullptr, *attn_scratch = nullptr;
   int pending_parts = 0;   // split-K partial sums of the last down-projection still to be added to h
@@ -156,6 +157,8 @@ struct RowMeta {
   const AttnMerge* merges;
   int n_merges;
   const int32_t* rowlist;   // batch rows of the shared-prefix items
+  const AttnItem* pf_items; // mixed pass: prefill items of the appended rows behind the decode rows
+  int n_pf_items;
   bool prefill;      // multi-row items (append / recompute) instead of single decode rows
   double kv_bytes;   // keys + values the attention of one layer has to read
   bool time_attn;
@@ -195,15 +198,16 @@ int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return v && *v ? atoi(v) : dflt;
 }
-GemmPlan plan_gemm(int M, int N, int K, bool can_split) {
+// part_rows: rows the partial-sum buffers hold (every split-K slice takes M of them)
+GemmPlan plan_gemm(int M, int N, int K, bool can_split, size_t part_rows) {
   // tuning overrides (development): RL_GEMM_TARGET_WGS, RL_GEMM_MAX_SPLITS
   static const int target = env_int("RL_GEMM_TARGET_WGS", 240);
   static const int max_splits = std::min(kMaxSplits, env_int("RL_GEMM_MAX_SPLITS", kMaxSplits));
   int tiles = ((N + 127) / 128) * ((M + 127) / 128);
   int s = 1;
-  if (can_split && M <= 256 && tiles < target) {
+  if (can_split && M <= 1024 && tiles < target) {   // decode steps, mixed steps and small appends
     s = (target + tiles / 2) / tiles;
-    s = std::min({s, max_splits, std::max(1, K / 256)});
+    s = std::min({s, max_splits, std::max(1, K / 256), (int)std::min<size_t>(part_rows / (size_t)M, 64)});
   }
   return GemmPlan{4, std::max(1, s)};
 }
@@ -219,7 +223,7 @@ void forward_mfma(rl_model* m, int M, const RowMeta& r) {
   for (int l = 0; l < md.L; l++) {
     const LayerW& w = m->layers[l];
     launch_add_rmsnorm(s, m->h, m->ph, pend, (size_t)M * H, (const bf16_t*)w.g_in, (bf16_t*)m->xa, M, H, md.eps);
-    GemmPlan pq = plan_gemm(M, QW, H, true);
+    GemmPlan pq = plan_gemm(M, QW, H, true, m->part_rows);
     int sq = launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wqkv, m->qkv, M, QW, H, EPI_STORE,
                               pq.splits, pq.nw);
     launch_qkrope<bf16_t, bf16_t, bf16_t, true>(s, m->qkv, sq, (size_t)M * QW, (const bf16_t*)w.gq,
@@ -228,14 +232,17 @@ void forward_mfma(rl_model* m, int M, const RowMeta& r) {
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l], s);
     launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.items, r.n_items, r.merges, r.n_merges,
                           r.rowlist, m->page_table, (bf16_t*)m->xo, m->attn_scratch, md, r.prefill);
+    if (r.n_pf_items > 0)
+      launch_attention_mfma(s, (const bf16_t*)m->qb, m->pools[l], r.pf_items, r.n_pf_items, nullptr, 0,
+                            nullptr, m->page_table, (bf16_t*)m->xo, m->attn_scratch, md, true);
     if (r.time_attn) (void)hipEventRecord(m->ev[2 * l + 1], s);
-    GemmPlan po = plan_gemm(M, H, qw, true);
+    GemmPlan po = plan_gemm(M, H, qw, true, m->part_rows);
     int so = launch_gemm_mfma(s, (const bf16_t*)m->xo, (const bf16_t*)w.wo, m->ph, M, H, qw, EPI_STORE,
                               po.splits, po.nw);
     launch_add_rmsnorm(s, m->h, m->ph, so, (size_t)M * H, (const bf16_t*)w.g_post, (bf16_t*)m->xa, M, H, md.eps);
-    GemmPlan pg = plan_gemm(M, 2 * I, H, false);
+    GemmPlan pg = plan_gemm(M, 2 * I, H, false, m->part_rows);
     launch_gemm_mfma(s, (const bf16_t*)m->xa, (const bf16_t*)w.wgu, m->xm, M, 2 * I, H, EPI_SWIGLU, 1, pg.nw);
-    GemmPlan pd = plan_gemm(M, H, I, true);
+    GemmPlan pd = plan_gemm(M, H, I, true, m->part_rows);
     pend = launch_gemm_mfma(s, (const bf16_t*)m->xm, (const bf16_t*)w.wdown, m->ph, M, H, I, EPI_STORE,
                             pd.splits, pd.nw);
   }
@@ -249,27 +256,29 @@ void forward_rows(rl_model* m, int M, const RowMeta& r) {
 }
 
 // final norm + lm-head for rows [r0, r0 + R) of m->h -> m->logits[0 .. R)
-void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done) {
+// M: rows of the forward pass (stride of its partial sums); norm_rows <= M: leading rows to normalise
+void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done, int norm_rows = -1) {
   hipStream_t s = m->stream;
   const ModelDims& md = m->md;
+  if (norm_rows < 0) norm_rows = M;
   if (m->mfma) {
     if (!norm_done) {
       launch_add_rmsnorm(s, m->h, m->ph, m->pending_parts, (size_t)M * md.H, (const bf16_t*)m->g_final,
-                         (bf16_t*)m->xa, M, md.H, md.eps);
+                         (bf16_t*)m->xa, norm_rows, md.H, md.eps);
       m->pending_parts = 0;
     }
     // r0 is a multiple of 128: skip whole A tiles
-    GemmPlan pl = plan_gemm(R, md.V, md.H, false);
+    GemmPlan pl = plan_gemm(R, md.V, md.H, false, m->part_rows);
     launch_gemm_mfma(s, (const bf16_t*)m->xa + (size_t)r0 * md.H, (const bf16_t*)m->lm_head, m->logits,
                      R, md.V, md.H, EPI_STORE, 1, pl.nw);
   } else if (m->bf16) {
     if (!norm_done)
-      launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, M, md.H, md.eps, false);
+      launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, norm_rows, md.H, md.eps, false);
     launch_gemm_generic<bf16_t, bf16_t>(s, (const bf16_t*)m->xa + (size_t)r0 * md.H,
                                         (const bf16_t*)m->lm_head, m->logits, R, md.V, md.H, false);
   } else {
     if (!norm_done)
-      launch_rmsnorm<float, float>(s, m->h, (const float*)m->g_final, (float*)m->xa, M, md.H, md.eps, false);
+      launch_rmsnorm<float, float>(s, m->h, (const float*)m->g_final, (float*)m->xa, norm_rows, md.H, md.eps, false);
     launch_gemm_generic<float, float>(s, (const float*)m->xa + (size_t)r0 * md.H,
                                       (const float*)m->lm_head, m->logits, R, md.V, md.H, false);
   }
@@ -482,7 +491,7 @@ int prefill(rl_model* m, const std::vector<std::pair<Traj*, int>>& work) {
     DevMeta dm;
     int rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, dm.rowlist, true, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, dm.rowlist, nullptr, 0, true, 0.0, false};
     forward_rows(m, M, r);
     HIPCHECK(hipGetLastError());
     HIPCHECK(hipStreamSynchronize(m->stream));
@@ -490,8 +499,13 @@ int prefill(rl_model* m, const std::vector<std::pair<Traj*, int>>& work) {
   return RL_OK;
 }
 
-int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature, uint64_t seed,
-                  const int32_t* forced, int32_t* ids_out, float* lp_out) {
+// extra: trajectories whose freshly appended tokens [n_cached, upto) still have to be prefilled.
+// Their rows ride behind the decode rows of the same forward pass (the weights are streamed once
+// for both); if they do not fit into one pass they are prefilled first, on their own.
+// *extra_done tells the caller whether that has happened when the function returns.
+int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, uint64_t seed,
+                const int32_t* forced, int32_t* ids_out, float* lp_out,
+                const std::vector<std::pair<Traj*, int>>* extra, bool* extra_done) {
   int rc = check_ids(ids, n);
   if (rc) return rc;
   if (!(temperature >= 0.0f)) return fail(RL_E_ARG, "negative temperature");
@@ -515,6 +529,17 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
   }
   if (need > m->n_free) return fail(RL_E_NOPAGES, "page pool exhausted");
   if (n == 0) return RL_OK;
+  // appended rows that ride along: they must fit into this pass together with the decode rows
+  int extra_rows = 0;
+  if (extra)
+    for (auto& w : *extra) extra_rows += std::max(0, w.second - w.first->n_cached);
+  if (extra && !extra->empty() && n + extra_rows > m->Mcap) {
+    rc = prefill(m, *extra);
+    *extra_done = true;
+    if (rc) return rc;
+    extra = nullptr;
+    extra_rows = 0;
+  }
   // commit page reservations (call order), then compute
   std::vector<int32_t> upd;
   for (Traj* t : ts)
@@ -540,10 +565,33 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
     kvb += (double)nt * 2.0 * m->md.nkv * m->md.d * m->el;
   }
   add_decode_items(m, st, ts);
+  const int n_dec_items = (int)st.items.size();
+  if (extra_rows > 0) {   // prefill rows behind the decode rows, prefill items behind the decode items
+    for (auto& w : *extra) {
+      Traj* t = w.first;
+      int cur = t->n_cached, upto = w.second;
+      if (cur >= upto) continue;
+      add_items(m, st, (int)st.tok.size(), upto - cur, t->slot, cur);
+      for (int p = cur; p < upto; p++) {
+        st.tok.push_back(t->tokens[p]);
+        st.pos.push_back(p);
+        st.slot.push_back(t->slot);
+      }
+    }
+    st.traj.resize(st.tok.size(), 0);
+    st.newpos.resize(st.tok.size(), 0);
+    if (forced) st.forced.resize(st.tok.size(), 0);
+  }
+  const int M = (int)st.tok.size();
   DevMeta dm;
   rc = upload_meta(m, st, &dm);
   if (rc) return rc;
-  bool timed = m->timing_every > 0 && (m->decode_steps % m->timing_every) == 0;
+  if (extra) {
+    for (auto& w : *extra) w.first->n_cached = std::max(w.first->n_cached, w.second);
+    *extra_done = true;
+  }
+  // mixed passes are left out of the kernel timing: its byte counts describe pure decode steps
+  bool timed = extra_rows == 0 && m->timing_every > 0 && (m->decode_steps % m->timing_every) == 0;
   m->decode_steps++;
   double kvu = 0.0;
   if (timed) {   // bytes of distinct pages: pages shared by forked trajectories count once
@@ -560,11 +608,11 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
       }
     }
   }
-  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(),
-            dm.rowlist, false, kvb, timed};
+  RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, n_dec_items, dm.merges, (int)st.merges.size(),
+            dm.rowlist, dm.items + n_dec_items, (int)st.items.size() - n_dec_items, false, kvb, timed};
   if (timed) (void)hipEventRecord(m->ev_step[0], m->stream);
-  forward_rows(m, n, r);
-  lm_head_rows(m, n, 0, n, false);
+  forward_rows(m, M, r);
+  lm_head_rows(m, M, 0, n, false, n);
   bool greedy = temperature == 0.0f;
   float c = (float)(1.4426950408889634 / (greedy ? 1.0 : (double)temperature));
   launch_sampler(m->stream, m->logits, (size_t)m->md.V, n, m->md.V, c, greedy ? 1 : 0, nullptr, seed,
@@ -600,6 +648,20 @@ int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature,
     lp_out[i] = m->h_lp[i];
   }
   return RL_OK;
+}
+
+int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature, uint64_t seed,
+                  const int32_t* forced, int32_t* ids_out, float* lp_out,
+                  const std::vector<std::pair<Traj*, int>>* extra = nullptr) {
+  bool extra_done = false;
+  int rc = decode_impl(m, ids, n, temperature, seed, forced, ids_out, lp_out, extra, &extra_done);
+  if (extra && !extra->empty() && !extra_done) {
+    // the decode part failed validation (or was empty): the append part still takes effect
+    std::string msg = g_err;
+    int prc = prefill(m, *extra);
+    if (rc == RL_OK) rc = prc; else g_err = msg;
+  }
+  return rc;
 }
 
 }  // namespace
@@ -730,7 +792,9 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   size_t ael = m->bf16 ? 2 : 4;
   TRY(m->dalloc((void**)&m->h, Mc * H * 4, true));
   // split-K partial sums: up to kMaxSplits slices of a decode-sized batch, or one prefill pass
-  size_t prow = m->mfma ? std::max<size_t>(Mc, (size_t)kMaxSplits * std::min(256, round_up(rt->max_trajectories, 128))) : Mc;
+  // up to kMaxSplits slices for passes of up to 1024 rows (plan_gemm also clamps to this capacity)
+  size_t prow = m->mfma ? std::max<size_t>(Mc, (size_t)kMaxSplits * std::min<size_t>(Mc, 1024)) : Mc;
+  m->part_rows = prow;
   TRY(m->dalloc((void**)&m->qkv, prow * (qw + 2 * kvw) * 4, true));
   if (m->mfma) TRY(m->dalloc((void**)&m->ph, prow * H * 4, true));
   TRY(m->dalloc(&m->xa, Mc * H * ael, true));
@@ -789,8 +853,10 @@ extern "C" int rl_model_get_config(const rl_model* m, rl_model_config* out) {
   return RL_OK;
 }
 
-extern "C" int rl_append_observation(rl_model* m, const int32_t* traj_ids, int32_t n,
-                                     const int32_t* tokens, const int32_t* lens) {
+// Host part of an append: validation, token / mask bookkeeping, page reservation and page-table
+// update.  On success *work lists the trajectories whose new tokens still need their keys / values.
+static int append_host(rl_model* m, const int32_t* traj_ids, int32_t n, const int32_t* tokens,
+                       const int32_t* lens, std::vector<std::pair<Traj*, int>>* work_out) {
   if (!m) return fail(RL_E_ARG, "null model");
   int rc = check_ids(traj_ids, n);
   if (rc) return rc;
@@ -841,7 +907,41 @@ extern "C" int rl_append_observation(rl_model* m, const int32_t* traj_ids, int32
     if (!t.tokens.empty()) work.push_back({&t, (int)t.tokens.size() - 1});
   }
   if (!upd.empty()) { rc = push_page_updates(m, upd); if (rc) return rc; }
+  *work_out = std::move(work);
+  return RL_OK;
+}
+
+extern "C" int rl_append_observation(rl_model* m, const int32_t* traj_ids, int32_t n,
+                                     const int32_t* tokens, const int32_t* lens) {
+  std::vector<std::pair<Traj*, int>> work;
+  int rc = append_host(m, traj_ids, n, tokens, lens, &work);
+  if (rc) return rc;
   return prefill(m, work);
+}
+
+extern "C" int rl_decode_step_with_appends(rl_model* m, const int32_t* app_ids, int32_t n_app,
+                                           const int32_t* app_tokens, const int32_t* app_lens,
+                                           const int32_t* ids, int32_t n, float temperature,
+                                           uint64_t rng_seed, int32_t* token_ids_out,
+                                           float* logprobs_out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (n > 0 && !token_ids_out) return fail(RL_E_ARG, "null output");
+  std::vector<std::pair<Traj*, int>> work;
+  int rc = append_host(m, app_ids, n_app, app_tokens, app_lens, &work);
+  if (rc) return rc;
+  return decode_common(m, ids, n, temperature, rng_seed, nullptr, token_ids_out, logprobs_out, &work);
+}
+
+extern "C" int rl_decode_step_forced_with_appends(rl_model* m, const int32_t* app_ids, int32_t n_app,
+                                                  const int32_t* app_tokens, const int32_t* app_lens,
+                                                  const int32_t* ids, int32_t n, float temperature,
+                                                  const int32_t* forced_token_ids, float* logprobs_out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (n > 0 && !forced_token_ids) return fail(RL_E_ARG, "null forced ids");
+  std::vector<std::pair<Traj*, int>> work;
+  int rc = append_host(m, app_ids, n_app, app_tokens, app_lens, &work);
+  if (rc) return rc;
+  return decode_common(m, ids, n, temperature, 0, forced_token_ids, nullptr, logprobs_out, &work);
 }
 
 extern "C" int rl_decode_step(rl_model* m, const int32_t* ids, int32_t n, float temperature,
@@ -961,7 +1061,7 @@ extern "C" int rl_debug_logits(rl_model* m, int32_t id, float* logits_out) {
   int rc = upload_meta(m, st, &dm);
   if (rc) return rc;
   RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(),
-            dm.rowlist, false, 0.0, false};
+            dm.rowlist, nullptr, 0, false, 0.0, false};
   forward_rows(m, 1, r);   // rewrites the key / value of position nt-1 with the same values
   lm_head_rows(m, 1, 0, 1, false);
   HIPCHECK(hipGetLastError());
@@ -1031,7 +1131,7 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
     DevMeta dm;
     rc = upload_meta(m, st, &dm);
     if (rc) return rc;
-    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, dm.rowlist, true, 0.0, false};
+    RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, 0, dm.rowlist, nullptr, 0, true, 0.0, false};
     forward_rows(m, M, r);
     if (m->mfma) {
       // fused pass: gather + final norm, lm-head with the log-softmax reduced in its epilogue (the

@@ -126,9 +126,13 @@ class MockTools:
 
 
 class ToolLoop:
-    def __init__(self, engine, plans, tools, temperature=1.0, rng_seed=3):
+    def __init__(self, engine, plans, tools, temperature=1.0, rng_seed=3, fuse=True):
+        """fuse: where the engine offers decode_step_with_appends, observations that have arrived
+        are appended inside the next decode call (one forward pass for both) instead of by a call
+        of their own."""
         self.engine, self.plans, self.tools = engine, {int(p.traj_id): p for p in plans}, tools
         self.temperature, self.rng_seed = float(temperature), int(rng_seed)
+        self.fuse = bool(fuse) and hasattr(engine, "decode_step_with_appends")
 
     def run(self, policy="continuous"):
         """Run every planned trajectory to its end.  Returns (outputs, stats): outputs[traj_id] =
@@ -154,15 +158,20 @@ class ToolLoop:
         waiting = set()
         parked = []        # lockstep: observations that arrived while the turn barrier is closed
 
+        staged = []        # fused mode: observations to append inside the next decode call
+
         def join(results):
             if not results:
                 return
-            t0 = time.perf_counter()
-            j_ids = np.array([r[0] for r in results], np.int32)
-            eng.append_observation(j_ids, np.concatenate([r[1] for r in results]).astype(np.int32),
-                                   np.array([len(r[1]) for r in results], np.int32))
-            stats["append_s"] += time.perf_counter() - t0
-            stats["append_calls"] += 1
+            if self.fuse:
+                staged.extend(results)
+            else:
+                t0 = time.perf_counter()
+                j_ids = np.array([r[0] for r in results], np.int32)
+                eng.append_observation(j_ids, np.concatenate([r[1] for r in results]).astype(np.int32),
+                                       np.array([len(r[1]) for r in results], np.int32))
+                stats["append_s"] += time.perf_counter() - t0
+                stats["append_calls"] += 1
             for tid, toks in results:
                 stats["appended"] += len(toks)
                 waiting.discard(tid)
@@ -198,7 +207,15 @@ class ToolLoop:
             # Generate: one token for every active trajectory
             a = np.array(active, np.int32)
             t0 = time.perf_counter()
-            tok, lp = eng.decode_step(a, self.temperature, self.rng_seed)
+            if staged:
+                tok, lp = eng.decode_step_with_appends(
+                    np.array([r[0] for r in staged], np.int32),
+                    np.concatenate([r[1] for r in staged]).astype(np.int32),
+                    np.array([len(r[1]) for r in staged], np.int32), a, self.temperature, self.rng_seed)
+                stats["fused_steps"] = stats.get("fused_steps", 0) + 1
+                staged.clear()
+            else:
+                tok, lp = eng.decode_step(a, self.temperature, self.rng_seed)
             stats["decode_s"] += time.perf_counter() - t0
             stats["decode_steps"] += 1
             stats["generated"] += len(active)

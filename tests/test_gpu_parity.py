@@ -139,6 +139,107 @@ def test_shared_prefix_decode_attention(name, group, prompt):
         assert np.abs(a[2] - b[2]).max() < TOL_BF16
 
 
+def _replay_fused(o, g, w):
+    """Like run_lockstep, but an append event directly followed by a decode event goes to the GPU
+    engine as ONE call (rl_decode_step_forced_with_appends); the oracle makes the two calls."""
+    evs, i, max_lp, fused = w.events, 0, 0.0, 0
+    live = set()
+    while i < len(evs):
+        ev = evs[i]
+        if ev[0] == "append" and i + 1 < len(evs) and evs[i + 1][0] == "decode":
+            dv = evs[i + 1]
+            o.append_observation(ev[1], ev[2], ev[3])
+            ids, lps = o.decode_step(dv[1], dv[2], dv[3])
+            glp = g.decode_step_forced_with_appends(ev[1], ev[2], ev[3], dv[1], dv[2], ids)
+            max_lp = max(max_lp, float(np.abs(glp - lps).max()))
+            live.update(int(t) for t in ev[1])
+            fused += 1
+            i += 2
+            continue
+        if ev[0] == "append":
+            o.append_observation(ev[1], ev[2], ev[3])
+            g.append_observation(ev[1], ev[2], ev[3])
+            live.update(int(t) for t in ev[1])
+        elif ev[0] == "fork":
+            o.fork(ev[1], ev[2])
+            g.fork(ev[1], ev[2])
+            live.update(int(t) for t in ev[2])
+        elif ev[0] == "decode":
+            ids, lps = o.decode_step(ev[1], ev[2], ev[3])
+            glp = g.decode_step_forced(ev[1], ev[2], ids)
+            max_lp = max(max_lp, float(np.abs(glp - lps).max()))
+        elif ev[0] == "release":
+            for t in ev[1]:
+                compare_records(o, g, int(t))
+            o.release(ev[1])
+            g.release(ev[1])
+            live.difference_update(int(t) for t in ev[1])
+        assert o.n_free_pages() == g.n_free_pages()
+        i += 1
+    for t in sorted(live):
+        compare_records(o, g, t)
+    return max_lp, fused
+
+
+@pytest.mark.parametrize("name,tol", [("tiny", TOL_FP32), ("tiny-bf16", TOL_BF16), ("small-d128", TOL_BF16),
+                                      ("small-g2", TOL_BF16)])
+def test_decode_step_with_appends_equals_the_two_calls(name, tol):
+    # Update + Generate in one forward pass: appended rows ride behind the decode rows; trajectories
+    # that get an observation decode in the same call.  Uniform turns (everybody appends, then
+    # everybody decodes) and ragged turns (a few append while the others keep decoding).
+    shape = SHAPES[name]
+    blob = make_weight_blob(shape, seed=7, weight_std=0.03, gain_std=0.1)
+    for w in (_bf16_workload(shape.vocab),
+              ragged_turns("ragged", shape.vocab, 7, 19, (1, 4), (2, 9), (3, 37), 200, 1.0)):
+        o, g = _pair(shape, blob)
+        max_lp, fused = _replay_fused(o, g, w)
+        print(name, w.name, max_lp, fused)
+        assert fused >= 1 and max_lp < tol
+
+
+def test_decode_step_with_appends_overflow_and_errors():
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=7, weight_std=0.03, gain_std=0.1)
+    # more appended rows than one pass holds: the append is prefilled on its own first
+    o, g = _pair(shape, blob, max_context=1024, max_trajectories=4, kv_pool_pages=200, max_batch_rows=128)
+    rng = np.random.default_rng(2)
+    t0 = rng.integers(0, shape.vocab, 40)
+    for e in (o, g):
+        e.append_observation([0, 1], t0, [25, 15])
+    big = rng.integers(0, shape.vocab, 300)
+    o.append_observation([1], big, [300])
+    ids, lps = o.decode_step([0, 1], 1.0, 4)
+    glp = g.decode_step_forced_with_appends([1], big, [300], [0, 1], 1.0, ids)
+    assert np.abs(glp - lps).max() < TOL_BF16
+    for t in (0, 1):
+        compare_records(o, g, t)
+        assert np.abs(o.debug_logits(t) - g.debug_logits(t)).max() < TOL_BF16
+    # append part valid, decode part invalid: the append takes effect, the error is the decode's
+    more = rng.integers(0, shape.vocab, 9)
+    with pytest.raises(rl.RolloutError) as ei:
+        g.decode_step_with_appends([0], more, [9], [0, 77], 1.0, 4)
+    assert ei.value.code == -2
+    o.append_observation([0], more, [9])
+    compare_records(o, g, 0)
+    assert np.abs(o.debug_logits(0) - g.debug_logits(0)).max() < TOL_BF16
+    # append part invalid: nothing changes
+    with pytest.raises(rl.RolloutError) as ei:
+        g.decode_step_with_appends([0], [shape.vocab], [1], [0], 1.0, 4)
+    assert ei.value.code == -4
+    compare_records(o, g, 0)
+    # empty append list = plain decode step; empty decode list = plain append
+    ids, lps = o.decode_step([0, 1], 0.0, 4)
+    gi, gl = g.decode_step_with_appends([], [], [], [0, 1], 0.0, 4)
+    assert np.array_equal(gi, ids) or np.abs(gl - lps).max() < TOL_BF16
+    g2 = rl.RolloutEngine(blob, max_context=256, max_trajectories=4, kv_pool_pages=64)
+    o2 = OracleEngine(blob, max_context=256, max_trajectories=4, kv_pool_pages=64)
+    o2.append_observation([3], t0, [40])
+    out = g2.decode_step_with_appends([3], t0, [40], [], 1.0, 4)
+    assert len(out[0]) == 0
+    compare_records(o2, g2, 3)
+    assert np.abs(o2.debug_logits(3) - g2.debug_logits(3)).max() < TOL_BF16
+
+
 def test_mfma_long_context_split_attention_and_chunked_prefill():
     # context long enough that decode attention is split over several workgroups, appended with a
     # row budget that forces several prefill passes and splits a trajectory across passes
