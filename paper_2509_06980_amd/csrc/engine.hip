@@ -71,6 +71,7 @@ struct rl_model {
   // work buffers
   int Mcap = 0, Rl = 0, rows_per_item = 1;
   size_t part_rows = 0;    // rows of the split-K partial-sum buffers qkv and ph
+  int attn_slots = 0;      // scratch slots for partial attention results
   bool cascade = false;    // shared-prefix decode attention
   float *h = nullptr, *qkv = nullptr, *ph = nullptr, *gu = nullptr, *logits = nullptr, *attn_scratch = nullptr;
   int pending_parts = 0;   // split-K partial sums of the last down-projection still to be added to h
@@ -305,8 +306,16 @@ struct DevMeta {
   int32_t* rowlist;
 };
 
+int check_pass(rl_model* m, const Staging& st, int slots_used);
+
 int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   size_t M = st.tok.size();
+  {
+    int slots = 0;
+    for (const AttnItem& it : st.items) slots = std::max(slots, it.part + 1);
+    int crc = check_pass(m, st, slots);
+    if (crc) return crc;
+  }
   static_assert(sizeof(AttnItem) == 32 && sizeof(AttnMerge) == 32, "metadata records are 8 ints");
   size_t need = 6 * M + 8 * st.items.size() + 8 * st.merges.size() + st.rowlist.size();
   if (need > m->meta_ints) return fail(RL_E_ARG, "internal: metadata staging too small");
@@ -388,7 +397,7 @@ void add_items(rl_model* m, Staging& st, int row0, int cnt, int slot, int pos0) 
 // then covers only its own remainder and a merge record joins the two.
 const int kAttnTargetWgs = 1024;
 const int kMinSharedPages = 8;
-void add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {
+int add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {   // returns scratch slots used
   int n = (int)st.pos.size();
   const int rpb = std::max(1, 16 / (m->md.nq / m->md.nkv));   // member rows per gather item
   // own_lo[i]: first page the row reads by itself; shared part records per row
@@ -458,6 +467,34 @@ void add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {
       st.items.push_back(AttnItem{i, 1, st.slot[i], st.pos[i], own_lo[i] + k * per,
                                   std::min(own_lo[i] + (k + 1) * per, np), next_part++, ts[i]->shared_lead << 8});
   }
+  return next_part;
+}
+
+// Host-side bounds of one forward pass, checked before anything is launched: a planning mistake
+// must surface as an error code, never as an out-of-bounds access on the GPU.
+int check_pass(rl_model* m, const Staging& st, int slots_used) {
+  const size_t M = st.tok.size();
+  if (M > (size_t)m->Mcap) return fail(RL_E_ARG, "internal: pass exceeds the row capacity");
+  if (m->mfma && slots_used > m->attn_slots) return fail(RL_E_ARG, "internal: attention scratch too small");
+  if (st.pos.size() != M || st.slot.size() != M) return fail(RL_E_ARG, "internal: row metadata mismatch");
+  const int maxp = m->md.max_pages_per_traj;
+  for (size_t i = 0; i < M; i++)
+    if (st.pos[i] < 0 || st.pos[i] / RL_PAGE >= maxp || st.slot[i] < 0 || st.slot[i] >= m->rt.max_trajectories)
+      return fail(RL_E_ARG, "internal: row position / slot out of range");
+  for (const AttnItem& it : st.items) {
+    const bool gather = it.gather & 1;
+    if (it.nrows < 1 || it.pg_lo < 0 || it.pg_hi > maxp || it.pg_lo > it.pg_hi || it.slot < 0 ||
+        it.slot >= m->rt.max_trajectories || it.part >= m->attn_slots ||
+        (gather ? (size_t)(it.row0 + it.nrows) > st.rowlist.size() : (size_t)(it.row0 + it.nrows) > M))
+      return fail(RL_E_ARG, "internal: attention item out of range");
+  }
+  for (int r : st.rowlist)
+    if (r < 0 || (size_t)r >= M) return fail(RL_E_ARG, "internal: row list out of range");
+  for (const AttnMerge& mg : st.merges)
+    if (mg.row < 0 || (size_t)mg.row >= M || mg.first < 0 || mg.first + mg.nparts > m->attn_slots ||
+        mg.sfirst < 0 || mg.sfirst + mg.snparts > m->attn_slots)
+      return fail(RL_E_ARG, "internal: merge record out of range");
+  return RL_OK;
 }
 
 // Chunked prefill of tokens[n_cached .. upto) for the listed trajectories (upto given per traj).
@@ -803,9 +840,11 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc(&m->qb, Mc * qw * ael, true));
   if (!m->mfma) TRY(m->dalloc((void**)&m->gu, Mc * 2 * I * 4, true));
   TRY(m->dalloc((void**)&m->logits, (size_t)m->Rl * V * 4));
-  if (m->mfma)
+  if (m->mfma) {
+    m->attn_slots = kAttnTargetWgs / c.n_kv_heads + 3 * rt->max_trajectories + 64;
     TRY(m->dalloc((void**)&m->attn_scratch,   // one slot per part of a cut decode row
-                  (size_t)(kAttnTargetWgs / c.n_kv_heads + 3 * rt->max_trajectories + 64) * c.n_kv_heads * 16 * 130 * 4));
+                  (size_t)m->attn_slots * c.n_kv_heads * 16 * 130 * 4));
+  }
   int nseg = sampler_nseg(V);
   TRY(m->dalloc((void**)&m->ss.segmax, (size_t)m->Rl * nseg * 4));
   TRY(m->dalloc((void**)&m->ss.segarg, (size_t)m->Rl * nseg * 4));

@@ -240,6 +240,109 @@ def test_decode_step_with_appends_overflow_and_errors():
     assert np.abs(o2.debug_logits(3) - g2.debug_logits(3)).max() < TOL_BF16
 
 
+@pytest.mark.parametrize("name,flags,rows,seed", [("small-d128", 0, 128, 1), ("small-d128", 2, 0, 2),
+                                                 ("small-g2", 2, 256, 3), ("tiny", 0, 0, 4),
+                                                 ("tiny-bf16", 0, 128, 5)])
+def test_random_call_sequences(name, flags, rows, seed):
+    # random interleavings of every entry point (append, decode, Update+Generate in one pass, fork,
+    # release, log-prob recompute) on both engines: integer state identical after every call,
+    # log-probs / logits within tolerance.  Small row budgets force multi-pass prefill and the
+    # fallback of the mixed pass; flag 2 = shared-prefix decode attention.
+    shape = SHAPES[name]
+    tol = TOL_FP32 if shape.weight_dtype == 0 else TOL_BF16
+    blob = make_weight_blob(shape, seed=20 + seed, weight_std=0.03, gain_std=0.1)
+    max_ctx, max_traj = 448, 8
+    kw = dict(max_context=max_ctx, max_trajectories=max_traj, kv_pool_pages=max_traj * (max_ctx // 16 + 1))
+    o = OracleEngine(blob, **kw)
+    g = rl.RolloutEngine(blob, flags=flags, max_batch_rows=rows, **kw)
+    rng = np.random.default_rng(seed)
+    length, next_id = {}, 0
+
+    def pick(ids, lo=1, hi=4):
+        ids = list(ids)
+        k = int(rng.integers(lo, min(hi, len(ids)) + 1))
+        return [int(x) for x in rng.choice(ids, size=k, replace=False)]
+
+    def draw_append():
+        cand = [t for t in length if length[t] < max_ctx - 80]
+        ids = pick(cand, 1, 3) if cand and rng.random() < 0.7 else []
+        nonlocal next_id
+        if len(length) + 1 <= max_traj and (not ids or rng.random() < 0.4):
+            ids.append(next_id)
+            next_id += 1
+        lens = [int(rng.integers(0, 70)) if t in length else int(rng.integers(1, 150)) for t in ids]
+        toks = rng.integers(0, shape.vocab, sum(lens))
+        return ids, toks, lens
+
+    worst = 0.0
+    for step in range(70):
+        live = [t for t in length if length[t] > 0]
+        op = rng.choice(["append", "decode", "mixed", "fork", "release", "recompute", "logits"],
+                        p=[0.2, 0.3, 0.2, 0.1, 0.06, 0.07, 0.07])
+        if op == "append" or not live:
+            ids, toks, lens = draw_append()
+            if not ids:
+                continue
+            o.append_observation(ids, toks, lens)
+            g.append_observation(ids, toks, lens)
+            for t, n in zip(ids, lens):
+                length[t] = length.get(t, 0) + n
+        elif op == "decode":
+            ids = [t for t in pick(live) if length[t] < max_ctx - 4]
+            for _ in range(int(rng.integers(1, 4))):
+                if not ids:
+                    break
+                T = float(rng.choice([1.0, 0.7, 0.0]))
+                tok, lps = o.decode_step(ids, T, 9)
+                glp = g.decode_step_forced(ids, T, tok)
+                worst = max(worst, float(np.abs(glp - lps).max()))
+                for t in ids:
+                    length[t] += 1
+        elif op == "mixed":
+            ids, toks, lens = draw_append()
+            for t, n in zip(ids, lens):
+                length[t] = length.get(t, 0) + n
+            dec = [t for t in length if 0 < length[t] < max_ctx - 4]
+            dec = pick(dec) if dec else []
+            o.append_observation(ids, toks, lens)
+            tok, lps = o.decode_step(dec, 1.0, 9)
+            glp = g.decode_step_forced_with_appends(ids, toks, lens, dec, 1.0, tok)
+            if len(dec):
+                worst = max(worst, float(np.abs(glp - lps).max()))
+            for t in dec:
+                length[t] += 1
+        elif op == "fork" and len(length) + 2 <= max_traj:
+            src = pick(live, 1, 1)[0]
+            dst = [next_id, next_id + 1][:int(rng.integers(1, 3))]
+            next_id += len(dst)
+            o.fork(src, dst)
+            g.fork(src, dst)
+            for d in dst:
+                length[d] = length[src]
+        elif op == "release":
+            ids = pick(list(length), 1, 2)
+            for t in ids:
+                compare_records(o, g, t)
+            o.release(ids)
+            g.release(ids)
+            for t in ids:
+                del length[t]
+        elif op == "recompute":
+            ids = pick(live, 1, 3)
+            T = float(rng.choice([1.0, 0.5]))
+            a, b = o.recompute_logprobs(ids, T), g.recompute_logprobs(ids, T)
+            assert a.shape == b.shape
+            worst = max(worst, float(np.abs(a - b).max()))
+        elif op == "logits":
+            t = pick(live, 1, 1)[0]
+            worst = max(worst, float(np.abs(o.debug_logits(t) - g.debug_logits(t)).max()))
+        assert o.n_free_pages() == g.n_free_pages(), (step, op)
+        assert worst < tol, (step, op, worst)
+    for t in length:
+        compare_records(o, g, t)
+    print(name, flags, rows, "worst", worst, "live", len(length))
+
+
 def test_mfma_long_context_split_attention_and_chunked_prefill():
     # context long enough that decode attention is split over several workgroups, appended with a
     # row budget that forces several prefill passes and splits a trajectory across passes
