@@ -455,16 +455,22 @@ def test_full_size_cfg3_launch_configuration_sampled_trajectory():
     o.append_observation([check], prompts[check // group], [prompt])
     ids = np.arange(n_traj, dtype=np.int32)
     worst = 0.0
+    chunk = None
     for turn in range(2):
         for step in range(3):
             tok, lp = o.decode_step([check], 1.0, 3)
             forced = rng.integers(0, shape.vocab, n_traj, dtype=np.int32)
             forced[check] = tok[0]
-            glp = g.decode_step_forced(ids, 1.0, forced)
+            if chunk is not None:
+                # first step after the observation: Update + Generate in one pass (3200 rows)
+                glp = g.decode_step_forced_with_appends(ids, chunk.reshape(-1), np.full(n_traj, obs, np.int32),
+                                                        ids, 1.0, forced)
+                chunk = None
+            else:
+                glp = g.decode_step_forced(ids, 1.0, forced)
             worst = max(worst, abs(float(glp[check]) - float(lp[0])))
         if turn == 0:
             chunk = rng.integers(0, shape.vocab, (n_traj, obs), dtype=np.int32)
-            g.append_observation(ids, chunk.reshape(-1), np.full(n_traj, obs, np.int32))
             o.append_observation([check], chunk[check], [obs])
     zo, zg = o.debug_logits(check), g.debug_logits(check)
     # At this depth and width bf16 rounding of activations and cached keys / values alone moves the
@@ -480,6 +486,10 @@ def test_full_size_cfg3_launch_configuration_sampled_trajectory():
     assert rms_gpu < 1.5 * rms_model + 1e-3
     assert max_gpu < 7.0 * rms_model
     assert worst < max(TOL_BF16, 4.0 * rms_model)
+    # masked log-prob pass at the full vocabulary (log-softmax reduced in the lm-head epilogue)
+    ro, rg = o.recompute_logprobs([check], 1.0), g.recompute_logprobs([check], 1.0)
+    assert ro.shape == rg.shape and np.count_nonzero(rg) == 6
+    assert np.abs(ro - rg).max() < max(TOL_BF16, 4.0 * rms_model)
     to, mo, _, po = o.traj_read(check)
     tg, mg, _, pg = g.traj_read(check)
     assert np.array_equal(to, tg) and np.array_equal(mo, mg)
