@@ -216,3 +216,23 @@ class OracleEngine:
             lp[np.array(t.mask, bool)] = 0.0
             out.append(lp)
         return np.concatenate(out).astype(np.float32) if out else np.zeros(0, np.float32)
+
+    # ---- GRPO objective over trajectories held in the cache ------------------------
+    def grpo_objective(self, traj_ids, group_size, rewards, temperature, clip_eps, beta,
+                       old_logprobs=None, ref_logprobs=None, eps_std=1e-6, std_ddof=0):
+        """Forward value of the masked GRPO objective (oracle/grpo.py) with the current
+        policy's log-probs recomputed over each trajectory.  old_logprobs / ref_logprobs:
+        concatenated like recompute_logprobs' output; old None = the log-probs recorded
+        when the tokens were sampled; ref None = no KL term."""
+        from .grpo import grpo_objective
+        ids = self._ids(traj_ids, must_exist=True)
+        new = self.recompute_logprobs(ids, temperature).astype(np.float64)
+        lens = [len(self.traj[i].tokens) for i in ids]
+        cuts = np.cumsum([0] + lens)
+        split = lambda a: [np.asarray(a, np.float64)[cuts[k]:cuts[k + 1]] for k in range(len(ids))]
+        masks = [np.array(self.traj[i].mask, np.uint8) for i in ids]
+        old = split(old_logprobs) if old_logprobs is not None else \
+            [np.array(self.traj[i].logp, np.float64) for i in ids]
+        ref = split(ref_logprobs) if ref_logprobs is not None else None
+        return grpo_objective(split(new), old, ref, masks, rewards, group_size, clip_eps, beta,
+                              eps_std, std_ddof)
