@@ -138,6 +138,15 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False):
             assert np.all(lp[off:off + glp.size][mask == 1] == 0.0)
             off += ctx[int(i)]
         stats["recompute_max_abs_diff"] = worst
+        # masked GRPO objective over the same trajectories (seeded rewards, the recomputed log-probs
+        # as reference policy): one more teacher-forced pass with the reduction on the device
+        G = 8 if ids.size % 8 == 0 else 1
+        rewards = np.random.default_rng(11).random(ids.size).astype(np.float32)
+        t0 = time.perf_counter()
+        obj = engine.grpo_objective(ids, G, rewards, 1.0, 0.2, 0.04, ref_logprobs=lp)
+        stats["objective_s"] = stats.get("objective_s", 0.0) + time.perf_counter() - t0
+        stats["objective"] = {"value": obj["objective"], "kl": obj["kl"], "n_tokens": obj["n_tokens"],
+                              "group_size": G}
         engine.release(ids)
     return n_gen
 
@@ -323,6 +332,10 @@ def main():
                       "tokens": stats["recompute_tokens"], "seconds": round(stats["recompute_s"], 3),
                       "max_abs_diff_vs_generation_logprobs": round(stats["recompute_max_abs_diff"], 5)}
         if stats.get("recompute_s") else None,
+        "grpo_objective": dict(stats["objective"],
+                               tokens_per_s=round(stats["recompute_tokens"] / stats["objective_s"], 1),
+                               seconds=round(stats["objective_s"], 3))
+        if stats.get("objective_s") else None,
         "decode_step_gpu_ms_sampled": round(step_gpu_ms / steps_timed, 3) if steps_timed else None,
         "decode_step_wall_ms_mean": round(stats["decode_s"] * 1e3 / max(stats["decode_steps"], 1), 3),
         "decode_by_turn": [

@@ -153,6 +153,36 @@ int64_t rl_free_pages(const rl_model* m);
 int rl_recompute_logprobs(rl_model* m, const int32_t* traj_ids, int32_t n, float temperature,
                           float* out);
 
+/*
+ * Forward value of the token-level masked GRPO objective over trajectories held in the cache
+ * (group sampling: Section 2.3, the multi-turn interaction example; tool results excluded from
+ * the loss: Section 2.2, last paragraph, and the loss mask of Section 2.3.2).  The paper prints
+ * no formula; this is the published GRPO objective restricted to the tokens the policy sampled:
+ *   A_i   = (r_i - mean_g(r)) / (std_g(r) + eps_std)      g = group of group_size consecutive ids
+ *   rho_t = exp(lp_new[t] - lp_old[t]),  k3_t = exp(d) - d - 1,  d = lp_ref[t] - lp_new[t]
+ *   J_i   = mean over sampled tokens t of  min(rho_t A_i, clip(rho_t, 1 - clip_eps, 1 + clip_eps) A_i) - beta k3_t
+ *   J     = mean over the n trajectories of J_i  (a trajectory without sampled tokens gives 0)
+ * lp_new is recomputed by a teacher-forced pass of the current weights at `temperature` (as
+ * rl_recompute_logprobs; the log-probs stay on the device).  All pointers are host memory.
+ *   rewards        [n] finite floats, one per trajectory
+ *   old_logprobs   one float per token of every listed trajectory, concatenated in call order
+ *                  (the layout rl_recompute_logprobs writes); NULL = the log-probs recorded when
+ *                  the tokens were sampled.  Values at appended tokens are ignored.
+ *   ref_logprobs   same layout, or NULL: no KL term (beta ignored, *kl_out = 0)
+ *   std_ddof       0: population standard deviation; 1: sample (needs group_size >= 2)
+ *   objective_out  J (to be maximised);  kl_out (may be NULL): mean over trajectories of their
+ *                  mean k3;  n_tokens_out (may be NULL): sampled tokens that took part;
+ *                  advantages_out (may be NULL): [n] doubles A_i
+ * Sums are float64 in a fixed order: results are reproducible run to run.  No state changes.
+ * Errors: ARG (n <= 0, n not a multiple of group_size, negative or non-finite parameter,
+ * non-finite reward, null pointer), BAD_TRAJ, DUP_ID, HIP.
+ */
+int rl_grpo_objective(rl_model* m, const int32_t* traj_ids, int32_t n, int32_t group_size,
+                      const float* rewards, const float* old_logprobs, const float* ref_logprobs,
+                      float temperature, double clip_eps, double beta, double eps_std,
+                      int32_t std_ddof, double* objective_out, double* kl_out,
+                      int64_t* n_tokens_out, double* advantages_out);
+
 /* Parity aids.  rl_debug_logits: next-token logits [vocab] of one trajectory, no state change.
  * rl_decode_step_forced: a decode step that appends forced_token_ids[i] instead of sampling and
  * returns its log-prob. */

@@ -12,7 +12,7 @@ EXPORTED_SYMBOLS = [
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
     "rl_decode_step_forced", "rl_sample_from_logits", "rl_uniform_u32", "rl_timing_enable",
     "rl_timing_read", "rl_timing_read_steps", "rl_measure_stream_read",
-    "rl_decode_step_with_appends", "rl_decode_step_forced_with_appends",
+    "rl_decode_step_with_appends", "rl_decode_step_forced_with_appends", "rl_grpo_objective",
 ]
 
 
@@ -73,6 +73,10 @@ def load_library():
     lib.rl_free_pages.argtypes = [C.c_void_p]
     lib.rl_free_pages.restype = C.c_int64
     lib.rl_recompute_logprobs.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_float, _F32P]
+    lib.rl_grpo_objective.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_int32, _F32P, _F32P, _F32P,
+                                      C.c_float, C.c_double, C.c_double, C.c_double, C.c_int32,
+                                      C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                      C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     lib.rl_debug_logits.argtypes = [C.c_void_p, C.c_int32, _F32P]
     lib.rl_sample_from_logits.argtypes = [_F32P, C.c_int32, C.c_int32, C.c_float, _U32P, _I32P, _F32P]
     lib.rl_uniform_u32.argtypes = [C.c_uint64, C.c_int32, C.c_int32]
@@ -246,6 +250,34 @@ class RolloutEngine:
         _check(self._lib.rl_recompute_logprobs(self._h, pi, ids.size, float(temperature),
                                                out.ctypes.data_as(_F32P)))
         return out
+
+    def grpo_objective(self, traj_ids, group_size, rewards, temperature, clip_eps, beta,
+                       old_logprobs=None, ref_logprobs=None, eps_std=1e-6, std_ddof=0):
+        """Masked GRPO objective of the listed trajectories (groups of group_size consecutive ids).
+        Returns dict(objective, kl, n_tokens, advantages)."""
+        ids, pi = _i32(traj_ids)
+        total = sum(self.traj_info(i)[0] for i in ids)
+        rew = np.ascontiguousarray(np.asarray(rewards, dtype=np.float32).reshape(-1))
+        if rew.size != ids.size:
+            raise ValueError("one reward per trajectory")
+
+        def lp_arg(a):
+            if a is None:
+                return None, None
+            a = np.ascontiguousarray(np.asarray(a, dtype=np.float32).reshape(-1))
+            if a.size != total:
+                raise ValueError("log-prob arrays hold one value per token of every listed trajectory")
+            return a, a.ctypes.data_as(_F32P)
+
+        old, p_old = lp_arg(old_logprobs)
+        ref, p_ref = lp_arg(ref_logprobs)
+        j, kl, nt = C.c_double(), C.c_double(), C.c_int64()
+        adv = np.empty(ids.size, np.float64)
+        _check(self._lib.rl_grpo_objective(
+            self._h, pi, ids.size, int(group_size), rew.ctypes.data_as(_F32P), p_old, p_ref,
+            float(temperature), float(clip_eps), float(beta), float(eps_std), int(std_ddof),
+            C.byref(j), C.byref(kl), C.byref(nt), adv.ctypes.data_as(C.POINTER(C.c_double))))
+        return dict(objective=j.value, kl=kl.value, n_tokens=nt.value, advantages=adv)
 
     def timing_enable(self, every):
         _check(self._lib.rl_timing_enable(self._h, int(every)))

@@ -14,6 +14,7 @@ SOURCES = {
     "kernels_mfma.hip": [],
     # the sampler's integer weights must not see fused multiply-adds
     "kernels_sampler.hip": ["-ffp-contract=off"],
+    "kernels_objective.hip": [],
     "engine.hip": [],
 }
 

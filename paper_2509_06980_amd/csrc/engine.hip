@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <functional>
 #include <queue>
 #include <string>
@@ -83,6 +84,10 @@ struct rl_model {
   float *d_lp = nullptr, *h_lp = nullptr;
   float *d_zt = nullptr, *d_lp_rows = nullptr, *h_lp_rows = nullptr;   // masked log-prob pass: Mcap rows
   uint8_t* d_mask = nullptr;
+  // objective pass: per-row old / reference log-probs, use flags and segments (device + pinned
+  // staging, the rewards behind them), per-trajectory advantages and accumulators, the result
+  float *d_gaux = nullptr, *h_gaux = nullptr;
+  double *d_gadv = nullptr, *d_gacc = nullptr, *d_gout = nullptr;
   // host state
   std::unordered_map<int32_t, Traj> traj;
   std::vector<int> free_slots;
@@ -855,6 +860,14 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc((void**)&m->d_mask, Mc));
   TRY(m->dalloc((void**)&m->d_zt, Mc * 4));
   TRY(m->dalloc((void**)&m->d_lp_rows, Mc * 4));
+  {
+    size_t T = (size_t)rt->max_trajectories;
+    TRY(m->dalloc((void**)&m->d_gaux, (3 * Mc + 4 * T + 4) * 4));
+    TRY(m->dalloc((void**)&m->d_gadv, T * 8));
+    TRY(m->dalloc((void**)&m->d_gacc, 3 * T * 8));
+    TRY(m->dalloc((void**)&m->d_gout, 3 * 8));
+    HIPTRY(hipHostMalloc((void**)&m->h_gaux, (3 * Mc + 4 * T + 4) * 4));
+  }
   m->meta_ints = 32 * Mc + 3 * 65536;
   TRY(m->dalloc((void**)&m->d_meta, m->meta_ints * 4));
   HIPTRY(hipHostMalloc((void**)&m->h_meta, m->meta_ints * 4));
@@ -880,6 +893,7 @@ extern "C" void rl_model_free(rl_model* m) {
   if (m->h_ids) (void)hipHostFree(m->h_ids);
   if (m->h_lp) (void)hipHostFree(m->h_lp);
   if (m->h_lp_rows) (void)hipHostFree(m->h_lp_rows);
+  if (m->h_gaux) (void)hipHostFree(m->h_gaux);
   for (auto e : m->ev) if (e) (void)hipEventDestroy(e);
   for (auto e : m->ev_step) if (e) (void)hipEventDestroy(e);
   if (m->stream) (void)hipStreamDestroy(m->stream);
@@ -1109,14 +1123,22 @@ extern "C" int rl_debug_logits(rl_model* m, int32_t id, float* logits_out) {
   return RL_OK;
 }
 
-extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n, float temperature,
-                                     float* out) {
-  if (!m) return fail(RL_E_ARG, "null model");
-  int rc = check_ids(ids, n);
-  if (rc) return rc;
-  if (!(temperature >= 0.0f) || (n > 0 && !out)) return fail(RL_E_ARG, "bad temperature or null output");
-  for (int i = 0; i < n; i++)
-    if (!m->traj.count(ids[i])) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+namespace {
+
+// What the objective pass adds to the teacher-forced pass: the log-probs of the tokens under the
+// old and the reference policy, one value per token of every listed trajectory, concatenated.
+struct ObjectiveCall {
+  const float* old_lp;   // null: the log-probs recorded when the tokens were sampled
+  const float* ref_lp;   // null: no KL term
+  double clip_eps, beta;
+};
+
+// Teacher-forced pass over whole trajectories.  out != null: the log-prob of every sampled token
+// goes to out (0 elsewhere).  obj != null: every sampled token's term of the objective is added to
+// the accumulators of its trajectory (cleared beforehand by the advantages kernel).
+int teacher_forced_pass(rl_model* m, const int32_t* ids, int32_t n, float temperature, float* out,
+                        const ObjectiveCall* obj) {
+  int rc = RL_OK;
   float c = (float)(1.4426950408889634 / (temperature == 0.0f ? 1.0 : (double)temperature));
   // flat list of rows: (trajectory, position p) for p in [0, n_tokens - 1); row p predicts token p+1
   struct Seg { Traj* t; size_t out_off; };
@@ -1125,17 +1147,52 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
   for (int i = 0; i < n; i++) {
     Traj& t = m->traj[ids[i]];
     segs.push_back({&t, off});
-    for (size_t k = 0; k < t.tokens.size(); k++) out[off + k] = 0.0f;
+    if (out)
+      for (size_t k = 0; k < t.tokens.size(); k++) out[off + k] = 0.0f;
     off += t.tokens.size();
   }
+  const size_t Mc = (size_t)m->Mcap;
+  float* g_old = m->h_gaux;
+  float* g_ref = m->h_gaux + Mc;
+  int32_t* g_use = (int32_t*)(m->h_gaux + 2 * Mc);
+  int32_t* g_seg = (int32_t*)(m->h_gaux + 3 * Mc);
+  // rows of this block of the pass -> terms of the objective (rows k in [0, K): log-prob in
+  // d_lp_rows[k], token dest[k] of trajectory number dtraj[k])
+  auto objective_rows = [&](int K, const std::vector<size_t>& dest, const std::vector<int>& dtraj,
+                            const std::vector<uint8_t>* mask) -> int {
+    if (K == 0) return RL_OK;
+    int nseg = 0;
+    for (int k = 0; k < K; k++) {
+      size_t at = dest[k];
+      const Traj* t = segs[dtraj[k]].t;
+      g_old[k] = obj->old_lp ? obj->old_lp[at] : t->logp[at - segs[dtraj[k]].out_off];
+      g_ref[k] = obj->ref_lp ? obj->ref_lp[at] : 0.0f;
+      g_use[k] = mask ? ((*mask)[k] == 0) : 1;
+      if (k == 0 || dtraj[k] != dtraj[k - 1]) {
+        if (nseg) g_seg[3 * nseg - 1] = k;
+        g_seg[3 * nseg] = dtraj[k];
+        g_seg[3 * nseg + 1] = k;
+        nseg++;
+      }
+    }
+    g_seg[3 * nseg - 1] = K;
+    float* d = m->d_gaux;
+    HIPCHECK(hipMemcpyAsync(d, m->h_gaux, (3 * Mc + 3 * (size_t)nseg) * 4, hipMemcpyHostToDevice, m->stream));
+    launch_grpo_terms(m->stream, m->d_lp_rows, d, obj->ref_lp ? d + Mc : nullptr, (const int32_t*)(d + 2 * Mc),
+                      (const int32_t*)(d + 3 * Mc), nseg, m->d_gadv, obj->clip_eps, obj->beta, m->d_gacc);
+    HIPCHECK(hipGetLastError());
+    return RL_OK;
+  };
   Staging st;
   std::vector<size_t> dest;   // output index of each row's log-prob
+  std::vector<int> dtraj;     // number (in call order) of each row's trajectory
   size_t si = 0;
   int cur = 0;
   int cap = m->Mcap;
   while (si < segs.size()) {
     st.clear();
     dest.clear();
+    dtraj.clear();
     while (si < segs.size() && (int)st.tok.size() < cap) {
       Traj* t = segs[si].t;
       int upto = (int)t->tokens.size() - 1;
@@ -1149,6 +1206,7 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
         st.forced.push_back(t->tokens[p + 1]);
         st.mask.push_back(t->mask[p + 1]);
         dest.push_back(segs[si].out_off + p + 1);
+        dtraj.push_back((int)si);
       }
       cur += take;
     }
@@ -1165,6 +1223,7 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
           st.traj[nsel] = k;
           st.newpos[nsel] = st.forced[k];
           dest[nsel] = dest[k];
+          dtraj[nsel] = dtraj[k];
           nsel++;
         }
     DevMeta dm;
@@ -1187,10 +1246,12 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
       }
       m->pending_parts = 0;
       HIPCHECK(hipGetLastError());
-      if (nsel > 0)
+      if (obj && (rc = objective_rows(nsel, dest, dtraj, nullptr))) return rc;
+      if (out && nsel > 0)
         HIPCHECK(hipMemcpyAsync(m->h_lp_rows, m->d_lp_rows, (size_t)nsel * 4, hipMemcpyDeviceToHost, m->stream));
       HIPCHECK(hipStreamSynchronize(m->stream));
-      for (int k = 0; k < nsel; k++) out[dest[k]] = m->h_lp_rows[k];
+      if (out)
+        for (int k = 0; k < nsel; k++) out[dest[k]] = m->h_lp_rows[k];
       continue;
     }
     for (int r0 = 0; r0 < M; r0 += m->Rl) {
@@ -1199,11 +1260,73 @@ extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n,
       launch_sampler(m->stream, m->logits, (size_t)m->md.V, R, m->md.V, c, 0, nullptr, 0, nullptr,
                      nullptr, dm.forced + r0, m->d_mask + r0, m->ss, nullptr, m->d_lp);
       HIPCHECK(hipGetLastError());
-      HIPCHECK(hipMemcpyAsync(m->h_lp, m->d_lp, (size_t)R * 4, hipMemcpyDeviceToHost, m->stream));
+      if (obj)
+        HIPCHECK(hipMemcpyAsync(m->d_lp_rows + r0, m->d_lp, (size_t)R * 4, hipMemcpyDeviceToDevice, m->stream));
+      if (out) HIPCHECK(hipMemcpyAsync(m->h_lp, m->d_lp, (size_t)R * 4, hipMemcpyDeviceToHost, m->stream));
       HIPCHECK(hipStreamSynchronize(m->stream));
-      for (int k = 0; k < R; k++) out[dest[r0 + k]] = m->h_lp[k];
+      if (out)
+        for (int k = 0; k < R; k++) out[dest[r0 + k]] = m->h_lp[k];
+    }
+    if (obj) {
+      if ((rc = objective_rows(M, dest, dtraj, &st.mask))) return rc;
+      HIPCHECK(hipStreamSynchronize(m->stream));
     }
   }
+  return RL_OK;
+}
+
+}  // namespace
+
+extern "C" int rl_recompute_logprobs(rl_model* m, const int32_t* ids, int32_t n, float temperature,
+                                     float* out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  int rc = check_ids(ids, n);
+  if (rc) return rc;
+  if (!(temperature >= 0.0f) || (n > 0 && !out)) return fail(RL_E_ARG, "bad temperature or null output");
+  for (int i = 0; i < n; i++)
+    if (!m->traj.count(ids[i])) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  return teacher_forced_pass(m, ids, n, temperature, out, nullptr);
+}
+
+extern "C" int rl_grpo_objective(rl_model* m, const int32_t* ids, int32_t n, int32_t group_size,
+                                 const float* rewards, const float* old_logprobs,
+                                 const float* ref_logprobs, float temperature, double clip_eps,
+                                 double beta, double eps_std, int32_t std_ddof, double* objective_out,
+                                 double* kl_out, int64_t* n_tokens_out, double* advantages_out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  int rc = check_ids(ids, n);
+  if (rc) return rc;
+  if (n <= 0 || !rewards || !objective_out) return fail(RL_E_ARG, "no trajectories, or null rewards or output");
+  if (group_size <= 0 || n % group_size != 0) return fail(RL_E_ARG, "trajectories must form whole groups");
+  if (std_ddof != 0 && !(std_ddof == 1 && group_size >= 2))
+    return fail(RL_E_ARG, "std_ddof must be 0, or 1 with groups of at least two");
+  if (!(temperature >= 0.0f) || !(clip_eps >= 0.0) || !(eps_std >= 0.0) || !(beta >= 0.0) ||
+      !std::isfinite(clip_eps) || !std::isfinite(beta) || !std::isfinite(eps_std))
+    return fail(RL_E_ARG, "bad temperature, clip_eps, beta or eps_std");
+  for (int i = 0; i < n; i++) {
+    if (!m->traj.count(ids[i])) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+    if (!std::isfinite(rewards[i])) return fail(RL_E_ARG, "reward is not finite");
+  }
+  const size_t Mc = (size_t)m->Mcap, T = (size_t)m->rt.max_trajectories;
+  float* h_rew = m->h_gaux + 3 * Mc + 3 * T + 3;   // behind the per-block staging: not reused during the pass
+  float* d_rew = m->d_gaux + 3 * Mc + 3 * T + 3;
+  memcpy(h_rew, rewards, (size_t)n * 4);
+  HIPCHECK(hipMemcpyAsync(d_rew, h_rew, (size_t)n * 4, hipMemcpyHostToDevice, m->stream));
+  launch_grpo_advantages(m->stream, d_rew, n, group_size, eps_std, std_ddof, m->d_gadv, m->d_gacc);
+  HIPCHECK(hipGetLastError());
+  ObjectiveCall oc{old_logprobs, ref_logprobs, clip_eps, beta};
+  rc = teacher_forced_pass(m, ids, n, temperature, nullptr, &oc);
+  if (rc) return rc;
+  launch_grpo_finish(m->stream, m->d_gacc, n, m->d_gout);
+  HIPCHECK(hipGetLastError());
+  double res[3];
+  HIPCHECK(hipMemcpyAsync(res, m->d_gout, sizeof(res), hipMemcpyDeviceToHost, m->stream));
+  if (advantages_out)
+    HIPCHECK(hipMemcpyAsync(advantages_out, m->d_gadv, (size_t)n * 8, hipMemcpyDeviceToHost, m->stream));
+  HIPCHECK(hipStreamSynchronize(m->stream));
+  *objective_out = res[0];
+  if (kl_out) *kl_out = res[1];
+  if (n_tokens_out) *n_tokens_out = (int64_t)res[2];
   return RL_OK;
 }
 

@@ -134,6 +134,19 @@ void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, in
                     const int32_t* row_newpos, const int32_t* forced, const uint8_t* out_mask,
                     SamplerScratch sc, int32_t* ids_out, float* logp_out);
 
+// Masked GRPO objective (forward value).  advantages: adv[i] of trajectory i within its group of G
+// consecutive rewards, (r - mean) / (std + eps_std), std with divisor G - ddof; also clears the 3 n
+// accumulators acc.  terms: for every row k of segment (traj, k0, k1) with use[k] != 0 adds
+// min(rho A, clip(rho, 1 -+ clip_eps) A) - beta k3 (rho = exp(lp - old_lp), k3 from ref_lp - lp;
+// ref_lp null: no KL term) to the trajectory's accumulators.  finish: out[0] = mean over
+// trajectories of their mean term, out[1] = likewise for k3, out[2] = number of tokens.
+void launch_grpo_advantages(hipStream_t s, const float* rewards, int n, int G, double eps_std, int ddof,
+                            double* adv, double* acc);
+void launch_grpo_terms(hipStream_t s, const float* lp, const float* old_lp, const float* ref_lp,
+                       const int32_t* use, const int32_t* segs, int nseg, const double* adv,
+                       double clip_eps, double beta, double* acc);
+void launch_grpo_finish(hipStream_t s, const double* acc, int n, double* out);
+
 // copy one page (all kv heads) within a layer pool: dst page <- src page; n pairs
 void launch_copy_pages(hipStream_t s, KvPool pool, const int32_t* src_dst_pairs, int n_pairs,
                        size_t page_bytes);

@@ -613,3 +613,97 @@ def test_full_size_cfg2_shape_sampled_trajectories():
         tg, mg = g.traj_read(c)[:2]
         assert np.array_equal(to, tg) and np.array_equal(mo, mg)
     g.close()
+
+
+# ---- masked GRPO objective over the cached trajectories -------------------------------------
+def _grpo_rollout(o, g, shape, n_groups, G, prompt, turns, seed):
+    """Same multi-turn group rollout on both engines (ids taken from the oracle)."""
+    rng = np.random.default_rng(seed)
+    ids = []
+    for q in range(n_groups):
+        first = q * G
+        toks = rng.integers(0, shape.vocab, prompt + q)
+        for e in (o, g):
+            e.append_observation([first], toks, [len(toks)])
+            if G > 1:
+                e.fork(first, list(range(first + 1, first + G)))
+        ids += list(range(first, first + G))
+    for turn, (n_gen, n_obs) in enumerate(turns):
+        act = [i for i in ids if (i + turn) % 3 != 0 or turn == 0]     # some trajectories stop early
+        for _ in range(n_gen):
+            tok, _ = o.decode_step(act, 1.0, 17)
+            g.decode_step_forced(act, 1.0, tok)
+        if n_obs:
+            lens = [n_obs + (i % 3) for i in act]
+            obs = rng.integers(0, shape.vocab, sum(lens))
+            for e in (o, g):
+                e.append_observation(act, obs, lens)
+    return ids
+
+
+@pytest.mark.parametrize("name,flags,tol,rows,ddof", [
+    ("tiny", 0, TOL_FP32, 0, 0), ("tiny-bf16", 0, TOL_BF16, 0, 1), ("small-d128", 0, TOL_BF16, 0, 0),
+    ("small-d128", 0, TOL_BF16, 128, 1), ("small-d128", 1, TOL_BF16, 128, 0)])
+def test_grpo_objective_matches_oracle(name, flags, tol, rows, ddof):
+    shape = SHAPES[name]
+    blob = make_weight_blob(shape, seed=14, weight_std=0.03, gain_std=0.1)
+    kw = dict(max_context=512, max_trajectories=16, kv_pool_pages=200)
+    if rows:
+        kw["max_batch_rows"] = rows        # trajectories then span several blocks of the pass
+    o, g = _pair(shape, blob, flags=flags, **kw)
+    G = 4
+    ids = _grpo_rollout(o, g, shape, 3, G, 37, [(9, 11), (6, 20), (12, 0)], seed=8)
+    rng = np.random.default_rng(3)
+    rewards = rng.random(len(ids)).astype(np.float32)
+    rewards[4:8] = 0.5                                       # a group with equal rewards: advantages 0
+    base = o.recompute_logprobs(ids, 1.0)
+    old = (base + rng.normal(0, 0.3, base.size)).astype(np.float32)     # off-policy: clipping is active
+    ref = (base + rng.normal(0, 0.2, base.size)).astype(np.float32)
+    for kwargs in (dict(), dict(old_logprobs=old), dict(old_logprobs=old, ref_logprobs=ref)):
+        beta = 0.04 if "ref_logprobs" in kwargs else 0.0
+        want = o.grpo_objective(ids, G, rewards, 1.0, 0.2, beta, std_ddof=ddof, **kwargs)
+        got = g.grpo_objective(ids, G, rewards, 1.0, 0.2, beta, std_ddof=ddof, **kwargs)
+        assert got["n_tokens"] == want["n_tokens"] > 0
+        assert np.abs(got["advantages"] - want["advantages"]).max() < 1e-12
+        assert np.all(got["advantages"][4:8] == 0.0)
+        # an error d of a log-prob changes its ratio by a factor e^d and its k3 by about |e^(ref-new) - 1| d
+        o_old = old if "old_logprobs" in kwargs else np.concatenate([o.traj_read(i)[2] for i in ids])
+        mask = np.concatenate([o.traj_read(i)[1] for i in ids]) == 0
+        rho_max = float(np.exp(base - o_old)[mask].max())
+        k_max = float(np.abs(np.expm1(ref - base))[mask].max()) if beta else 0.0
+        bound = (np.exp(tol) - 1.0) * (np.abs(want["advantages"]).max() * rho_max + beta * (k_max + 1.0)) + 1e-9
+        assert abs(got["objective"] - want["objective"]) < bound, (kwargs.keys(), got, want, bound)
+        assert abs(got["kl"] - want["kl"]) < (np.exp(tol) - 1.0) * (k_max + 1.0) + 1e-12
+        if not kwargs:
+            assert abs(got["objective"]) < bound      # on-policy: mean of group-normalised advantages
+        again = g.grpo_objective(ids, G, rewards, 1.0, 0.2, beta, std_ddof=ddof, **kwargs)
+        assert again["objective"] == got["objective"] and again["kl"] == got["kl"]     # fixed summation order
+    # no state change: the cache still decodes like the oracle's
+    tok, lp = o.decode_step(ids[:3], 1.0, 5)
+    assert np.abs(g.decode_step_forced(ids[:3], 1.0, tok) - lp).max() < tol
+
+
+def test_grpo_objective_errors():
+    shape = SHAPES["tiny"]
+    blob = make_weight_blob(shape, seed=14)
+    g = rl.RolloutEngine(blob, max_context=64, max_trajectories=8, kv_pool_pages=32)
+    g.append_observation([0, 1, 2, 3], np.arange(12), [3, 3, 3, 3])
+    g.decode_step([0, 1, 2, 3], 1.0, 1)
+    ok = g.grpo_objective([0, 1, 2, 3], 2, [1, 0, 0, 1], 1.0, 0.2, 0.0)
+    assert ok["n_tokens"] == 4 and np.allclose(ok["advantages"], [1, -1, -1, 1], atol=1e-5)
+    for bad, code in [(dict(traj_ids=[0, 1, 2], rewards=[1, 0, 0]), -1),
+                      (dict(traj_ids=[0, 1, 2, 9]), -2),
+                      (dict(traj_ids=[0, 1, 1, 2]), -3),
+                      (dict(rewards=[1, 0, np.nan, 1]), -1),
+                      (dict(clip_eps=-0.1), -1), (dict(beta=-1.0), -1),
+                      (dict(group_size=1, std_ddof=1), -1), (dict(std_ddof=2), -1),
+                      (dict(temperature=-1.0), -1)]:
+        a = dict(traj_ids=[0, 1, 2, 3], group_size=2, rewards=[1, 0, 0, 1], temperature=1.0, clip_eps=0.2, beta=0.0)
+        a.update(bad)
+        with pytest.raises(rl.RolloutError) as ei:
+            g.grpo_objective(**a)
+        assert ei.value.code == code, bad
+    # trajectories without sampled tokens contribute nothing
+    g.append_observation([5, 6], np.arange(8), [4, 4])
+    out = g.grpo_objective([5, 6], 2, [1, 0], 1.0, 0.2, 0.0)
+    assert out["objective"] == 0.0 and out["n_tokens"] == 0
