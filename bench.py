@@ -51,11 +51,11 @@ def recorded_traffic(config):
     return None
 
 
-def run_rollout(engine, w, shape, stats, fuse_appends=False):
+def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
     """Replay the workload once (free-running sampling); returns generated token count.
     fuse_appends: an append event directly followed by a decode event is issued as one call
     (rl_decode_step_with_appends); its time is booked under the decode step."""
-    kvtok = shape.kv_bytes_per_token()
+    kvtok = shape.kv_bytes_per_token() * kv_scale      # kv_scale 0.5: 8-bit cache variant
     wbytes = shape.decode_weight_bytes()
     ctx = {}
     n_gen = 0
@@ -236,6 +236,8 @@ def main():
     ap.add_argument("--timing-every", type=int, default=16)
     ap.add_argument("--shared-prefix-attention", action="store_true",
                     help="decode attention reads a forked group's shared pages once per block of members")
+    ap.add_argument("--fp8-kv-cache", action="store_true",
+                    help="variant, never the headline: keys / values cached as E4M3 codes (half the cache bytes)")
     ap.add_argument("--fuse-appends", action="store_true",
                     help="issue an append that is directly followed by a decode step as one call")
     ap.add_argument("--tool-loop", action="store_true",
@@ -265,7 +267,9 @@ def main():
     t0 = time.perf_counter()
     eng = rl.RolloutEngine(blob, max_context=w.max_context + 16, max_trajectories=w.n_trajectories,
                            kv_pool_pages=pages,
-                           flags=rl.FLAG_SHARED_PREFIX_ATTENTION if args.shared_prefix_attention else 0)
+                           flags=(rl.FLAG_SHARED_PREFIX_ATTENTION if args.shared_prefix_attention else 0) |
+                           (rl.FLAG_FP8_KV_CACHE if args.fp8_kv_cache else 0))
+    kv_scale = 0.5 if args.fp8_kv_cache else 1.0
     t_load = time.perf_counter() - t0
     print(f"[bench] {args.config}: {w.description}; blob {blob.nbytes / 1e9:.2f} GB in {t_blob:.1f}s, "
           f"load {t_load:.1f}s, pool {pages} pages", file=sys.stderr, flush=True)
@@ -273,7 +277,7 @@ def main():
     for i in range(args.warmup):
         t0 = time.perf_counter()
         run_rollout(eng, w, shape, dict(append_s=0.0, decode_s=0.0, decode_bytes=0.0, decode_steps=0),
-                    args.fuse_appends)
+                    args.fuse_appends, kv_scale)
         print(f"[bench] warmup {i}: {time.perf_counter() - t0:.2f}s", file=sys.stderr, flush=True)
 
     eng.timing_enable(args.timing_every)
@@ -283,7 +287,7 @@ def main():
     t0 = time.perf_counter()
     n_gen = 0
     for i in range(args.steps):
-        n_gen += run_rollout(eng, w, shape, stats, args.fuse_appends)
+        n_gen += run_rollout(eng, w, shape, stats, args.fuse_appends, kv_scale)
         print(f"[bench] step {i}: {time.perf_counter() - t0:.2f}s elapsed", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -301,7 +305,7 @@ def main():
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "frac_of_measured_stream_read": round(achieved / stream_gbs, 4),
-                    "traffic": recorded_traffic(args.config) if args.scale == 1.0 else None,
+                    "traffic": recorded_traffic(args.config) if args.scale == 1.0 and not args.fp8_kv_cache else None,
                     "achieved_counting_shared_pages_per_trajectory": round(attn_bytes / (attn_ms * 1e-3) / 1e9, 1),
                     "kernel": "attention_mfma_kernel" if eng.config["head_dim"] == 128 and
                     eng.config["weight_dtype"] == 1 else "attention_generic_kernel",
@@ -318,7 +322,8 @@ def main():
                    "observation_tokens_per_step": w.n_observation, "prompt_tokens": w.n_prompt,
                    "decode_steps_per_step": w.n_decode_steps, "max_context": w.max_context,
                    "scale": args.scale, "shared_prefix_attention": bool(args.shared_prefix_attention),
-                   "fuse_appends": bool(args.fuse_appends)},
+                   "fuse_appends": bool(args.fuse_appends),
+                   "kv_cache": "fp8_e4m3 (variant: not the bf16 contract of the headline)" if args.fp8_kv_cache else "bf16"},
         "measured_stream_read_GBs": round(stream_gbs, 1),
         "decode_only_tokens_per_s": round(n_gen / stats["decode_s"], 1) if stats["decode_s"] else None,
         "decode_step_hbm": {"achieved": round(stats["decode_bytes"] / stats["decode_s"] / 1e9, 1),

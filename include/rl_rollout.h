@@ -70,6 +70,13 @@ typedef struct {
                                      forked group share (Section 2.3.2: several samples per prompt)
                                      once per group of 16 / (n_q / n_kv) members instead of once per
                                      member, and merges the result with each member's own pages */
+#define RL_FLAG_FP8_KV_CACHE 4 /* keys (after QK-norm and RoPE) and values are cached as OCP FP8 E4M3
+                                     codes: nearest code, ties to even, magnitudes above 448 stored
+                                     as +-448; read back exactly and used in bf16 arithmetic.  Halves
+                                     the bytes of the cache and of the decode attention.  A variant
+                                     with its own numerical contract (the paper describes no cache);
+                                     bf16 models with head_dim 128 on the MFMA kernels only, else
+                                     rl_model_load fails with ARG */
 
 /*
  * Load a model: parse the blob (64-byte header: "RLW1", u32 version 1, the rl_model_config

@@ -42,7 +42,11 @@ def forward_bf16_model(m: OracleModel, tokens, points=ALL_POINTS):
             q = rmsnorm(q, m.w(p + "g_q"), m.rms_eps)
             k = rmsnorm(k, m.w(p + "g_k"), m.rms_eps)
         q = r(rope(q, pos, m.rope_theta), "q")
-        k = r(rope(k, pos, m.rope_theta), "k")
+        k = rope(k, pos, m.rope_theta)
+        if m.kv_quant is not None:      # 8-bit cache: keys and values go from fp32 straight to the cache format
+            k, v = m.kv_quant(k), m.kv_quant((a @ m.w(p + "w_v").T).reshape(n, m.n_kv_heads, d))
+        else:
+            k = r(k, "k")
         o = np.zeros((n, m.n_q_heads, d))
         for j in range(m.n_q_heads):
             g = j // rep

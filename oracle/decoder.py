@@ -39,6 +39,7 @@ class OracleModel:
         el = 2 if self.weight_dtype == 1 else 4
         self._raw = raw
         self._el = el
+        self.kv_quant = None     # None: keys / values cached as computed; else x -> x as the cache returns it
         self._t = {}
         off = _HDR
 
@@ -121,7 +122,10 @@ def _qkv(m, l, a, pos):
     if m.qk_norm:
         q = rmsnorm(q, m.w(p + "g_q"), m.rms_eps)
         k = rmsnorm(k, m.w(p + "g_k"), m.rms_eps)
-    return rope(q, pos, m.rope_theta), rope(k, pos, m.rope_theta), v
+    q, k = rope(q, pos, m.rope_theta), rope(k, pos, m.rope_theta)
+    if m.kv_quant is not None:      # 8-bit cache variant: keys and values as the cache returns them
+        k, v = m.kv_quant(k), m.kv_quant(v)
+    return q, k, v
 
 
 def _mlp(m, l, h):

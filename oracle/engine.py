@@ -41,8 +41,13 @@ def _ceil_div(a, b):
 
 class OracleEngine:
     def __init__(self, blob, max_context=4096, max_trajectories=256, kv_pool_pages=1024,
-                 page_tokens=16):
+                 page_tokens=16, kv_cache_dtype=None):
         self.model = blob if isinstance(blob, OracleModel) else OracleModel(blob)
+        if kv_cache_dtype == "fp8_e4m3":      # 8-bit cache variant (oracle/fp8.py)
+            from .fp8 import e4m3_round
+            self.model.kv_quant = e4m3_round
+        elif kv_cache_dtype is not None:
+            raise ValueError("kv_cache_dtype must be None or 'fp8_e4m3'")
         self.P = page_tokens
         self.max_context = max_context
         self.max_trajectories = max_trajectories

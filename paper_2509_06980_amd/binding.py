@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = [
 
 FLAG_GENERIC_KERNELS = 1            # RL_FLAG_GENERIC_KERNELS
 FLAG_SHARED_PREFIX_ATTENTION = 2    # RL_FLAG_SHARED_PREFIX_ATTENTION
+FLAG_FP8_KV_CACHE = 4               # RL_FLAG_FP8_KV_CACHE
 
 
 class RolloutError(RuntimeError):

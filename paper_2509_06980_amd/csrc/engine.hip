@@ -59,6 +59,7 @@ struct rl_model {
   ModelDims md{};
   bool bf16 = false, mfma = false;
   size_t el = 4;
+  size_t kv_el = 4;        // bytes per cached key / value element (1: 8-bit cache)
   hipStream_t stream = nullptr;
   std::vector<void*> allocs;  // everything to hipFree
   // weights
@@ -604,7 +605,7 @@ int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, u
     st.newpos.push_back(nt);
     if (forced) st.forced.push_back(forced[i]);
     max_pos = std::max(max_pos, nt - 1);
-    kvb += (double)nt * 2.0 * m->md.nkv * m->md.d * m->el;
+    kvb += (double)nt * 2.0 * m->md.nkv * m->md.d * m->kv_el;
   }
   add_decode_items(m, st, ts);
   const int n_dec_items = (int)st.items.size();
@@ -639,7 +640,7 @@ int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, u
   if (timed) {   // bytes of distinct pages: pages shared by forked trajectories count once
     if (m->page_stamp.size() != m->refcount.size()) m->page_stamp.assign(m->refcount.size(), 0);
     m->stamp++;
-    double tokb = 2.0 * m->md.nkv * m->md.d * m->el;
+    double tokb = 2.0 * m->md.nkv * m->md.d * m->kv_el;
     for (Traj* t : ts) {
       int nt = (int)t->tokens.size();
       for (int pg = 0; pg * RL_PAGE < nt; pg++) {
@@ -739,9 +740,15 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   m->el = el;
   m->mfma = m->bf16 && mfma_shape_ok(c) && !(rt->flags & RL_FLAG_GENERIC_KERNELS);
   m->cascade = (rt->flags & RL_FLAG_SHARED_PREFIX_ATTENTION) != 0;
+  const bool kv_fp8 = (rt->flags & RL_FLAG_FP8_KV_CACHE) != 0;
+  if (kv_fp8 && !m->mfma) {
+    delete m;
+    return fail(RL_E_ARG, "the 8-bit cache needs a bf16 model on the MFMA kernels (head_dim 128)");
+  }
+  m->kv_el = kv_fp8 ? 1 : el;
   int max_pages = (rt->max_context + RL_PAGE - 1) / RL_PAGE;
   m->md = ModelDims{c.n_layers, c.hidden, c.n_q_heads, c.n_kv_heads, c.head_dim, c.intermediate,
-                    c.vocab, c.rms_eps, c.qk_norm, max_pages};
+                    c.vocab, c.rms_eps, c.qk_norm, max_pages, kv_fp8 ? 1 : 0};
   // prefill items: 4 waves x RL_PREFILL_CB column blocks x 16/G rows
   m->rows_per_item = m->mfma ? 4 * RL_PREFILL_CB * (16 / (c.n_q_heads / c.n_kv_heads)) : 1;
   int rc = RL_OK;
@@ -816,7 +823,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
     HIPTRY(hipMemcpy(m->rope_cs, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
   }
   // ---- KV pool ----
-  m->page_bytes = (size_t)c.n_kv_heads * RL_PAGE * d * el;
+  m->page_bytes = (size_t)c.n_kv_heads * RL_PAGE * d * m->kv_el;
   m->pools.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; l++) {
     TRY(m->dalloc(&m->pools[l].k, m->page_bytes * rt->kv_pool_pages, true));

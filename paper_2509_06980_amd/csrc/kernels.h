@@ -32,7 +32,7 @@ struct AttnMerge {
 };
 
 struct KvPool {      // one layer
-  void* k;           // [pages][n_kv][16 * d] elements
+  void* k;           // [pages][n_kv][16 * d] elements (bf16 / fp32, or one byte each: 8-bit cache)
   void* v;
 };
 
@@ -41,6 +41,7 @@ struct ModelDims {
   float eps;
   int qk_norm;
   int max_pages_per_traj;  // row stride of the page table
+  int kv_fp8;              // keys / values cached as E4M3 codes (MFMA path, head_dim 128 only)
 };
 
 // ---- generic kernels (TA: activation type, TW: weight type; float or bf16_t) -------------

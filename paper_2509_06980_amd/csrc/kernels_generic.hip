@@ -372,7 +372,8 @@ template void launch_gemm_generic<bf16_t, bf16_t>(hipStream_t, const bf16_t*, co
 // head_dim 128, bf16, MFMA cache layout: grid (M, ceil(heads / 16)), block 256.  Sixteen lanes
 // own one head: lane `sub` holds dims 4 sub .. 4 sub + 3 and their rotate-half partners 64 + ...,
 // so partial sums arrive as 16-byte loads (all issued before the first add) and q, k leave as
-// 8-byte stores.
+// 8-byte stores.  FP8: keys and values go from fp32 straight to E4M3 codes (8-bit cache layout).
+template <bool FP8>
 __global__ __launch_bounds__(256) void qkrope128_kernel(
     const float* __restrict__ qkv, int n_part, size_t part_stride, const bf16_t* __restrict__ gq,
     const bf16_t* __restrict__ gk, const float* __restrict__ rope_cs,
@@ -409,12 +410,22 @@ __global__ __launch_bounds__(256) void qkrope128_kernel(
   for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 16);
   bf16_t* blk = nullptr;
   const int tok = pos & (RL_PAGE - 1);
+  int page_id = 0, kvh_id = 0;
   if (!is_q) {
-    const int page = page_table[(size_t)row_slot[row] * pt_stride + (pos >> 4)];
-    const int kvh = is_v ? hd - nq - nkv : hd - nq;
-    blk = (is_v ? vpool : kpool) + ((size_t)page * nkv + kvh) * (RL_PAGE * 128);
+    page_id = page_table[(size_t)row_slot[row] * pt_stride + (pos >> 4)];
+    kvh_id = is_v ? hd - nq - nkv : hd - nq;
+    blk = (is_v ? vpool : kpool) + ((size_t)page_id * nkv + kvh_id) * (RL_PAGE * 128);
   }
   if (is_v) {
+    if constexpr (FP8) {
+      uint8_t* blk8 = (uint8_t*)(is_v ? vpool : kpool) + ((size_t)page_id * nkv + kvh_id) * (RL_PAGE * 128);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        blk8[vswz8_off(tok, sub * 4 + e)] = f2e4m3(a[e]);
+        blk8[vswz8_off(tok, 64 + sub * 4 + e)] = f2e4m3(b[e]);
+      }
+      return;
+    }
 #pragma unroll
     for (int e = 0; e < 4; e++) {
       blk[vswz_off(tok, sub * 4 + e)] = f2bf(a[e]);
@@ -432,6 +443,20 @@ __global__ __launch_bounds__(256) void qkrope128_kernel(
     for (int e = 0; e < 4; e++) { a[e] = a[e] * inv * gl[e]; b[e] = b[e] * inv * gh[e]; }
   }
   const float c[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, sn[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+  if constexpr (FP8) {
+    if (!is_q) {   // 4 consecutive dims = 4 consecutive bytes of one lane slot
+      uint8_t* blk8 = (uint8_t*)kpool + ((size_t)page_id * nkv + kvh_id) * (RL_PAGE * 128);
+      float r1[4], r2[4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        r1[e] = a[e] * c[e] - b[e] * sn[e];
+        r2[e] = b[e] * c[e] + a[e] * sn[e];
+      }
+      *(uint32_t*)(blk8 + kswz8_off(tok, sub * 4)) = f2e4m3x4(r1[0], r1[1], r1[2], r1[3]);
+      *(uint32_t*)(blk8 + kswz8_off(tok, 64 + sub * 4)) = f2e4m3x4(r2[0], r2[1], r2[2], r2[3]);
+      return;
+    }
+  }
   uint32_t y1[4], y2[4];
 #pragma unroll
   for (int e = 0; e < 4; e++) {
@@ -459,9 +484,16 @@ void launch_qkrope(hipStream_t s, const float* qkv, int n_part, size_t part_stri
   if constexpr (SWZ) {
     if (md.d == 128 && n_part <= 8) {
       dim3 grid128(M, (md.nq + 2 * md.nkv + 15) / 16);
-      qkrope128_kernel<<<grid128, 256, 0, s>>>(qkv, n_part, part_stride, gq, gk, rope_cs, row_pos, row_slot,
-                                               page_table, qout, (bf16_t*)pool.k, (bf16_t*)pool.v, md.nq,
-                                               md.nkv, md.eps, md.qk_norm, md.max_pages_per_traj);
+      if (md.kv_fp8)
+        qkrope128_kernel<true><<<grid128, 256, 0, s>>>(qkv, n_part, part_stride, gq, gk, rope_cs, row_pos,
+                                                       row_slot, page_table, qout, (bf16_t*)pool.k,
+                                                       (bf16_t*)pool.v, md.nq, md.nkv, md.eps, md.qk_norm,
+                                                       md.max_pages_per_traj);
+      else
+        qkrope128_kernel<false><<<grid128, 256, 0, s>>>(qkv, n_part, part_stride, gq, gk, rope_cs, row_pos,
+                                                        row_slot, page_table, qout, (bf16_t*)pool.k,
+                                                        (bf16_t*)pool.v, md.nq, md.nkv, md.eps, md.qk_norm,
+                                                        md.max_pages_per_traj);
       return;
     }
   }

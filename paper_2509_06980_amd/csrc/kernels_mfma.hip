@@ -280,20 +280,22 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
 // finds them in L2, and so does the prefill kernel, which re-reads pages across waves and items.
 // The choice is made per wave, outside the page loop: inside it the compiler would merge the two
 // loads into one and drop the hint.
+// kpool / vpool are byte pointers; a (page, kv head) block is BLK bytes (4096: bf16, 2048: 8-bit
+// cache) that a wave reads as NLD 16-byte slots per lane (head_off = kv head * BLK + lane * 16).
 #define ATT_LOAD_PLAIN(KR, VR, PAGEID)                                        \
   {                                                                           \
-    const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
-    _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
-      KR[c] = *(const u32x4*)(kpool + base_ + c * 512);                       \
-      VR[c] = *(const u32x4*)(vpool + base_ + c * 512);                       \
+    const size_t base_ = (size_t)(PAGEID) * nkv * BLK + head_off;             \
+    _Pragma("unroll") for (int c = 0; c < NLD; c++) {                         \
+      KR[c] = *(const u32x4*)(kpool + base_ + c * 1024);                      \
+      VR[c] = *(const u32x4*)(vpool + base_ + c * 1024);                      \
     }                                                                         \
   }
 #define ATT_LOAD_STREAM(KR, VR, PAGEID)                                       \
   {                                                                           \
-    const size_t base_ = (size_t)(PAGEID) * nkv * 2048 + head_off;            \
-    _Pragma("unroll") for (int c = 0; c < 4; c++) {                           \
-      KR[c] = __builtin_nontemporal_load((const u32x4*)(kpool + base_ + c * 512)); \
-      VR[c] = __builtin_nontemporal_load((const u32x4*)(vpool + base_ + c * 512)); \
+    const size_t base_ = (size_t)(PAGEID) * nkv * BLK + head_off;             \
+    _Pragma("unroll") for (int c = 0; c < NLD; c++) {                         \
+      KR[c] = __builtin_nontemporal_load((const u32x4*)(kpool + base_ + c * 1024)); \
+      VR[c] = __builtin_nontemporal_load((const u32x4*)(vpool + base_ + c * 1024)); \
     }                                                                         \
   }
 #define ATT_PAGE(KR, VR, PG)                                                  \
@@ -334,6 +336,16 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
       acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0); \
     }                                                                         \
   }
+// 8-bit cache: the raw slots are first widened to the bf16 operand registers (exact).
+#define ATT_PAGE_ANY(KR, VR, PG)                                              \
+  if constexpr (FP8) {                                                        \
+    u32x4 kx_[4], vx_[4];                                                     \
+    expand_e4m3_block(KR, kx_);                                               \
+    expand_e4m3_block(VR, vx_);                                               \
+    ATT_PAGE(kx_, vx_, PG)                                                    \
+  } else {                                                                    \
+    ATT_PAGE(KR, VR, PG)                                                      \
+  }
 // The decode kernel's page loop (uses pt, pg0, pg1, pglast, head_off, kpool, vpool, nkv and the
 // buffers kA, vA, kB, vB of the enclosing kernel); LOAD is one of the two load macros.
 #define ATT_PAGE_LOOP(LOAD)                                                   \
@@ -347,13 +359,13 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
       int id_n2 = pt[min(pg + 2, pglast)];                                    \
       LOAD(kB, vB, id_nxt)                                                    \
       __builtin_amdgcn_sched_barrier(0);                                      \
-      ATT_PAGE(kA, vA, pg)                                                    \
+      ATT_PAGE_ANY(kA, vA, pg)                                                \
       __builtin_amdgcn_sched_barrier(0);                                      \
       /* page pg+1 is in B; request the table entry of pg+3, then pg+2 -> A */ \
       id_nxt = pt[min(pg + 3, pglast)];                                       \
       LOAD(kA, vA, id_n2)                                                     \
       __builtin_amdgcn_sched_barrier(0);                                      \
-      ATT_PAGE(kB, vB, pg + 1)                                                \
+      ATT_PAGE_ANY(kB, vB, pg + 1)                                            \
       __builtin_amdgcn_sched_barrier(0);                                      \
     }                                                                         \
   }
@@ -380,8 +392,9 @@ __device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
   *l_out = L;
 }
 
+template <bool FP8>
 __global__ __launch_bounds__(256) void attention_mfma_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kpool, const bf16_t* __restrict__ vpool,
+    const bf16_t* __restrict__ q, const char* __restrict__ kpool, const char* __restrict__ vpool,
     const AttnItem* __restrict__ items, const int32_t* __restrict__ rowlist,
     const int32_t* __restrict__ page_table, bf16_t* __restrict__ o, float* __restrict__ scratch,
     int nq, int nkv, int gshift, int pt_stride, float scale2) {
@@ -423,8 +436,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   // the loop defines registers conditionally; sched_barrier keeps the loads where they are
   // written, ahead of the arithmetic.
   const int pglast = max(pg1 - 1, pg0);
-  const size_t head_off = (size_t)kvh * 2048 + lane * 8;
-  u32x4 kA[4], vA[4], kB[4], vB[4];
+  constexpr int NLD = FP8 ? 2 : 4, BLK = FP8 ? 2048 : 4096;
+  const size_t head_off = (size_t)kvh * BLK + lane * 16;
+  u32x4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
   // a wave whose share of the pages starts behind the trajectory's shared leading pages streams
   if (pg0 >= (it.gather >> 8)) {
     ATT_PAGE_LOOP(ATT_LOAD_STREAM)
@@ -527,9 +541,9 @@ __device__ __forceinline__ void prefill_page(const u32x4 (&KR)[4], const u32x4 (
 // columns; the four waves read the same pages at about the same time (the later copies hit in
 // cache).  The running output is rescaled only on pages where some column's maximum moved.
 // No cross-wave merge is needed.
-template <int CB>
+template <int CB, bool FP8>
 __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kpool, const bf16_t* __restrict__ vpool,
+    const bf16_t* __restrict__ q, const char* __restrict__ kpool, const char* __restrict__ vpool,
     const AttnItem* __restrict__ items, const int32_t* __restrict__ page_table,
     bf16_t* __restrict__ o, int nq, int nkv, int gshift, int pt_stride, float scale2) {
   const int item_idx = blockIdx.x / nkv;
@@ -564,16 +578,26 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
     l[cb] = 0.f;
   }
   const int pglast = max(pg1 - 1, pg0);
-  const size_t head_off = (size_t)kvh * 2048 + lane * 8;
-  u32x4 kA[4], vA[4], kB[4], vB[4];
+  constexpr int NLD = FP8 ? 2 : 4, BLK = FP8 ? 2048 : 4096;
+  const size_t head_off = (size_t)kvh * BLK + lane * 16;
+  u32x4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
   // pages that end at or before the wave's first row are visible to all of its rows: no masking
   const int full_pages = (it.pos0 + wrow0 + 1) / RL_PAGE;
-#define PF_PAGE(KR, VR, PG)                                                   \
+#define PF_PAGE_BF16(KR, VR, PG)                                              \
   {                                                                           \
     if ((PG) < full_pages)                                                    \
       prefill_page<CB, false>(KR, VR, (PG), qreg, acc, m, l, mypos, g, scale2); \
     else if ((PG) < pg1)                                                      \
       prefill_page<CB, true>(KR, VR, (PG), qreg, acc, m, l, mypos, g, scale2); \
+  }
+#define PF_PAGE(KR, VR, PG)                                                   \
+  if constexpr (FP8) {                                                        \
+    u32x4 kx_[4], vx_[4];                                                     \
+    expand_e4m3_block(KR, kx_);                                               \
+    expand_e4m3_block(VR, vx_);                                               \
+    PF_PAGE_BF16(kx_, vx_, PG)                                                \
+  } else {                                                                    \
+    PF_PAGE_BF16(KR, VR, PG)                                                  \
   }
   if (pg0 < pg1) {
     int id_cur = pt[pg0];
@@ -593,6 +617,7 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
     }
   }
 #undef PF_PAGE
+#undef PF_PAGE_BF16
 #pragma unroll
   for (int cb = 0; cb < CB; cb++) {
     const float lt = quad_sum(l[cb]);
@@ -668,16 +693,24 @@ void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const At
   float scale2 = 1.4426950408889634f / sqrtf((float)md.d);
   int gshift = 0;
   while ((1 << gshift) < md.nq / md.nkv) gshift++;
+  const char* kp = (const char*)pool.k;
+  const char* vp = (const char*)pool.v;
+  const dim3 grid(n_items * md.nkv);
   if (prefill) {
-    attention_prefill_mfma_kernel<RL_PREFILL_CB><<<n_items * md.nkv, 256, 0, s>>>(
-        q, (const bf16_t*)pool.k, (const bf16_t*)pool.v, items, page_table, o, md.nq, md.nkv, gshift,
-        md.max_pages_per_traj, scale2);
+    if (md.kv_fp8)
+      attention_prefill_mfma_kernel<RL_PREFILL_CB, true><<<grid, 256, 0, s>>>(
+          q, kp, vp, items, page_table, o, md.nq, md.nkv, gshift, md.max_pages_per_traj, scale2);
+    else
+      attention_prefill_mfma_kernel<RL_PREFILL_CB, false><<<grid, 256, 0, s>>>(
+          q, kp, vp, items, page_table, o, md.nq, md.nkv, gshift, md.max_pages_per_traj, scale2);
     return;
   }
-  attention_mfma_kernel<<<n_items * md.nkv, 256, 0, s>>>(q, (const bf16_t*)pool.k,
-                                                        (const bf16_t*)pool.v, items, rowlist,
-                                                        page_table, o, scratch, md.nq, md.nkv, gshift,
-                                                        md.max_pages_per_traj, scale2);
+  if (md.kv_fp8)
+    attention_mfma_kernel<true><<<grid, 256, 0, s>>>(q, kp, vp, items, rowlist, page_table, o, scratch,
+                                                     md.nq, md.nkv, gshift, md.max_pages_per_traj, scale2);
+  else
+    attention_mfma_kernel<false><<<grid, 256, 0, s>>>(q, kp, vp, items, rowlist, page_table, o, scratch,
+                                                      md.nq, md.nkv, gshift, md.max_pages_per_traj, scale2);
   if (n_merges > 0)
     attention_merge_kernel<<<dim3(n_merges, md.nkv), 256, 0, s>>>(scratch, merges, o, md.nq, md.nkv,
                                                                   gshift);

@@ -66,6 +66,44 @@ __host__ __device__ __forceinline__ int vswz_off(int tok, int d) {
   return ((((jb >> 1) * 64 + lane) * 2 + (jb & 1)) << 2) + (tok & 3);
 }
 
+// 8-bit cache variant (OCP FP8 E4M3 codes, head_dim 128, 2 KB for K and 2 KB for V per block): the
+// same operand orders with one byte per element, packed so that a lane still loads 16 bytes at a
+// time.  K: the 16-byte lane slot holds the lane's 8 dims of two consecutive 32-dim operands.
+// V: the slot holds the lane's 4 tokens of four consecutive 16-dim operands.
+__host__ __device__ __forceinline__ int kswz8_off(int tok, int d) {
+  int lane = tok + (((d >> 3) & 3) << 4);
+  return (((((d >> 6) * 64 + lane) << 1) + ((d >> 5) & 1)) << 3) + (d & 7);
+}
+__host__ __device__ __forceinline__ int vswz8_off(int tok, int d) {
+  int jb = d >> 4, lane = (d & 15) + ((tok >> 2) << 4);
+  return (((((jb >> 2) * 64 + lane) << 2) + (jb & 3)) << 2) + (tok & 3);
+}
+// E4M3 code of x: round to nearest even, magnitudes above the largest finite value stored as it.
+__device__ __forceinline__ uint32_t f2e4m3x4(float a, float b, float c, float d) {
+  a = fminf(fmaxf(a, -448.f), 448.f); b = fminf(fmaxf(b, -448.f), 448.f);
+  c = fminf(fmaxf(c, -448.f), 448.f); d = fminf(fmaxf(d, -448.f), 448.f);
+  int p = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+  p = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, p, true);
+  return (uint32_t)p;
+}
+__device__ __forceinline__ uint8_t f2e4m3(float a) { return (uint8_t)(f2e4m3x4(a, a, a, a) & 0xffu); }
+// Four E4M3 codes (one 32-bit word) -> four bf16 (exact), element order kept.
+__device__ __forceinline__ void e4m3x4_to_bf16(uint32_t w, uint32_t* lo, uint32_t* hi) {
+  *lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+  *hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true));
+}
+// Two raw 16-byte lane slots of an 8-bit block -> the four 16-byte operand registers that the
+// bf16 block of the same tokens would have delivered (same rule for keys and values).
+__device__ __forceinline__ void expand_e4m3_block(const u32x4 (&raw)[2], u32x4 (&out)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    uint32_t a, b, c, d;
+    e4m3x4_to_bf16(raw[i >> 1][2 * (i & 1)], &a, &b);
+    e4m3x4_to_bf16(raw[i >> 1][2 * (i & 1) + 1], &c, &d);
+    out[i] = (u32x4){a, b, c, d};
+  }
+}
+
 template <bool SWZ>
 __device__ __forceinline__ int kblk_off(int tok, int d, int D) {
   return SWZ ? kswz_off(tok, d) : tok * D + d;

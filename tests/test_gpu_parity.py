@@ -707,3 +707,106 @@ def test_grpo_objective_errors():
     g.append_observation([5, 6], np.arange(8), [4, 4])
     out = g.grpo_objective([5, 6], 2, [1, 0], 1.0, 0.2, 0.0)
     assert out["objective"] == 0.0 and out["n_tokens"] == 0
+
+
+# ---- 8-bit (E4M3) key / value cache variant --------------------------------------------------
+def _fp8_pair(shape, blob, **kw):
+    kw.setdefault("max_context", 1024)
+    kw.setdefault("max_trajectories", 16)
+    kw.setdefault("kv_pool_pages", 256)
+    okw = {k: v for k, v in kw.items() if k != "max_batch_rows"}
+    return (OracleEngine(blob, kv_cache_dtype="fp8_e4m3", **okw),
+            rl.RolloutEngine(blob, flags=rl.FLAG_FP8_KV_CACHE, **kw))
+
+
+def _fp8_model_rms(o, traj):
+    """What the arithmetic type costs on this trajectory under the 8-bit cache: rms distance of the
+    logits between the oracle (codes chosen from exact keys / values) and the bf16 error model with
+    the same cache rule (codes chosen from bf16-perturbed ones: near a rounding boundary the code
+    flips, a full E4M3 step on that element)."""
+    from oracle.bf16_error_model import forward_bf16_model
+    from oracle.decoder import forward_full
+    toks = o.traj_read(traj)[0]
+    d = forward_bf16_model(o.model, toks) - forward_full(o.model, toks)
+    return float(np.sqrt((d ** 2).mean()))
+
+
+@pytest.mark.parametrize("name", ["small-d128", "small-g2", "small-g1", "small-g8"])
+def test_fp8_kv_cache_lockstep(name):
+    shape = SHAPES[name]
+    blob = make_weight_blob(shape, seed=2, weight_std=0.03, gain_std=0.1)
+    o, g = _fp8_pair(shape, blob)
+    r = run_lockstep(o, g, _bf16_workload(shape.vocab), check_logits_every=3, logit_rows=6)
+    rms = _fp8_model_rms(o, 0)
+    print(name, r, "model rms", rms)
+    # the oracle with the cache rule is the reference; the bound is what bf16 arithmetic in front of
+    # the 8-bit rounding costs (several times the plain bf16 bound), measured by the error model
+    assert r["max_logit_err"] < 8.0 * rms and r["max_logp_err"] < 8.0 * rms, (r, rms)
+    rec, ref = g.recompute_logprobs([0, 4], 1.0), o.recompute_logprobs([0, 4], 1.0)
+    assert rec.shape == ref.shape and np.abs(rec - ref).max() < 8.0 * rms
+    # the variant really is a different contract: it is further from the unquantised oracle
+    # than the bf16 bound, and the unquantised GPU path is further from this oracle
+    o2, g2 = _pair(shape, blob)
+    run_lockstep(o2, g2, _bf16_workload(shape.vocab))
+    z8, zb = o.debug_logits(0), o2.debug_logits(0)
+    assert np.abs(z8 - zb).max() > TOL_BF16
+    assert np.abs(g.debug_logits(0) - z8).max() < np.abs(g2.debug_logits(0) - z8).max()
+
+
+def test_fp8_kv_cache_long_context_split_attention_chunked_prefill_and_mixed_pass():
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=3, weight_std=0.03, gain_std=0.1)
+    o, g = _fp8_pair(shape, blob, max_context=1024, max_trajectories=4, kv_pool_pages=200, max_batch_rows=384)
+    rng = np.random.default_rng(1)
+    lens = [700, 523]
+    toks = rng.integers(0, shape.vocab, sum(lens))
+    for e in (o, g):
+        e.append_observation([0, 1], toks, lens)
+        e.fork(1, [2])
+    rms = _fp8_model_rms(o, 1)
+    for step in range(3):
+        for t in (0, 1, 2):
+            assert np.abs(o.debug_logits(t) - g.debug_logits(t)).max() < 8.0 * rms
+        ids, lps = o.decode_step([0, 1, 2], 1.0, 5)
+        glp = g.decode_step_forced([0, 1, 2], 1.0, ids)
+        assert np.abs(glp - lps).max() < 8.0 * rms
+    # Update + Generate in one pass
+    obs = rng.integers(0, shape.vocab, 40)
+    o.append_observation([2, 0], obs, [25, 15])
+    ids, lps = o.decode_step([0, 1, 2], 1.0, 5)
+    glp = g.decode_step_forced_with_appends([2, 0], obs, [25, 15], [0, 1, 2], 1.0, ids)
+    assert np.abs(glp - lps).max() < 8.0 * rms
+    for t in (0, 1, 2):
+        compare_records(o, g, t)
+    # the objective pass reads the same cache
+    out = g.grpo_objective([0, 1, 2], 3, [1.0, 0.0, 0.5], 1.0, 0.2, 0.0)
+    want = o.grpo_objective([0, 1, 2], 3, [1.0, 0.0, 0.5], 1.0, 0.2, 0.0)
+    assert out["n_tokens"] == want["n_tokens"] and abs(out["objective"] - want["objective"]) < 8.0 * rms * 2
+
+
+def test_fp8_kv_cache_needs_the_mfma_path():
+    for name, flags in [("tiny", rl.FLAG_FP8_KV_CACHE), ("tiny-bf16", rl.FLAG_FP8_KV_CACHE),
+                        ("small-d128", rl.FLAG_FP8_KV_CACHE | rl.FLAG_GENERIC_KERNELS)]:
+        shape = SHAPES[name]
+        with pytest.raises(rl.RolloutError) as ei:
+            rl.RolloutEngine(make_weight_blob(shape, seed=1), flags=flags, max_context=64,
+                             max_trajectories=2, kv_pool_pages=8)
+        assert ei.value.code == -1
+
+
+def test_fp8_kv_cache_is_bit_reproducible():
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=5, weight_std=0.03, gain_std=0.1)
+    w = _bf16_workload(shape.vocab)
+    runs = []
+    for _ in range(2):
+        g = rl.RolloutEngine(blob, flags=rl.FLAG_FP8_KV_CACHE, max_context=1024, max_trajectories=16,
+                             kv_pool_pages=256)
+        rec = replay(g, w)
+        runs.append((rec, [g.traj_read(t) for t in range(6)]))
+        g.close()
+    assert runs[0][0].keys() == runs[1][0].keys() and len(runs[0][0]) == 6
+    for t in runs[0][0]:
+        assert runs[0][0][t] == runs[1][0][t]
+    for a, b in zip(runs[0][1], runs[1][1]):
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
