@@ -43,7 +43,7 @@ def trace_summary(path):
     acc = defaultdict(lambda: [0, 0.0])
     with open(path, newline="") as f:
         for r in csv.DictReader(f):
-            if not r["Kernel_Name"].startswith("attention_mfma_kernel"):
+            if "attention_mfma_kernel<false>" not in r["Kernel_Name"]:
                 continue
             g = int(r.get("Grid_Size_X") or r.get("Grid_Size"))
             a = acc[g]
@@ -111,8 +111,9 @@ def main():
 
     kf, kw = calib(fetch), calib(write)
     grid = n_traj * n_kv * 256                      # decode launches: one workgroup per (trajectory, kv head)
-    fa = fetch["attention_mfma_kernel"][grid]
-    wa = write["attention_mfma_kernel"][grid]
+    name = "attention_mfma_kernel<false>"           # the bf16-cache instance of the decode kernel
+    fa = fetch[name][grid]
+    wa = write[name][grid]
     f_bytes = sum(fa) / len(fa) * 1024.0 * kf
     w_bytes = sum(wa) / len(wa) * 1024.0 * kw
     print("# HBM traffic of attention_mfma_kernel, cfg3 rollout (Qwen3-4B shape, 128 trajectories)\n")

@@ -298,11 +298,24 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
       VR[c] = __builtin_nontemporal_load((const u32x4*)(vpool + base_ + c * 1024)); \
     }                                                                         \
   }
+// Operand register i of a page buffer: the 16-byte slot itself (bf16 cache), or half a raw slot
+// of the 8-bit cache widened to bf16 (exact) just before use, so that no widened page stays live.
+template <bool FP8, int N>
+__device__ __forceinline__ u32x4 att_operand(const u32x4 (&R)[N], int i) {
+  if constexpr (FP8) {
+    uint32_t a, b, c, d;
+    e4m3x4_to_bf16(R[i >> 1][2 * (i & 1)], &a, &b);
+    e4m3x4_to_bf16(R[i >> 1][2 * (i & 1) + 1], &c, &d);
+    return (u32x4){a, b, c, d};
+  } else {
+    return R[i];
+  }
+}
 #define ATT_PAGE(KR, VR, PG)                                                  \
   {                                                                           \
     f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};                                    \
     _Pragma("unroll") for (int c = 0; c < 4; c++)                             \
-      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KR[c]), \
+      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, att_operand<FP8>(KR, c)), \
                                                   __builtin_bit_cast(bf16x8, qreg[c]), S, 0, 0, 0); \
     float sv[4], mx = ATT_NEG;                                                \
     bool vis[4];                                                              \
@@ -327,24 +340,15 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
     m = mn;                                                                   \
     _Pragma("unroll") for (int jp = 0; jp < 4; jp++) {                        \
       s16x4 v0, v1;                                                           \
-      v0[0] = (short)(VR[jp][0] & 0xffff); v0[1] = (short)(VR[jp][0] >> 16);  \
-      v0[2] = (short)(VR[jp][1] & 0xffff); v0[3] = (short)(VR[jp][1] >> 16);  \
-      v1[0] = (short)(VR[jp][2] & 0xffff); v1[1] = (short)(VR[jp][2] >> 16);  \
-      v1[2] = (short)(VR[jp][3] & 0xffff); v1[3] = (short)(VR[jp][3] >> 16);  \
+      const u32x4 vr_ = att_operand<FP8>(VR, jp);                             \
+      v0[0] = (short)(vr_[0] & 0xffff); v0[1] = (short)(vr_[0] >> 16);        \
+      v0[2] = (short)(vr_[1] & 0xffff); v0[3] = (short)(vr_[1] >> 16);        \
+      v1[0] = (short)(vr_[2] & 0xffff); v1[1] = (short)(vr_[2] >> 16);        \
+      v1[2] = (short)(vr_[3] & 0xffff); v1[3] = (short)(vr_[3] >> 16);        \
       _Pragma("unroll") for (int i = 0; i < 4; i++) { acc[2 * jp][i] *= alpha; acc[2 * jp + 1][i] *= alpha; } \
       acc[2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v0, pb, acc[2 * jp], 0, 0, 0); \
       acc[2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(v1, pb, acc[2 * jp + 1], 0, 0, 0); \
     }                                                                         \
-  }
-// 8-bit cache: the raw slots are first widened to the bf16 operand registers (exact).
-#define ATT_PAGE_ANY(KR, VR, PG)                                              \
-  if constexpr (FP8) {                                                        \
-    u32x4 kx_[4], vx_[4];                                                     \
-    expand_e4m3_block(KR, kx_);                                               \
-    expand_e4m3_block(VR, vx_);                                               \
-    ATT_PAGE(kx_, vx_, PG)                                                    \
-  } else {                                                                    \
-    ATT_PAGE(KR, VR, PG)                                                      \
   }
 // The decode kernel's page loop (uses pt, pg0, pg1, pglast, head_off, kpool, vpool, nkv and the
 // buffers kA, vA, kB, vB of the enclosing kernel); LOAD is one of the two load macros.
@@ -359,14 +363,41 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
       int id_n2 = pt[min(pg + 2, pglast)];                                    \
       LOAD(kB, vB, id_nxt)                                                    \
       __builtin_amdgcn_sched_barrier(0);                                      \
-      ATT_PAGE_ANY(kA, vA, pg)                                                \
+      ATT_PAGE(kA, vA, pg)                                                \
       __builtin_amdgcn_sched_barrier(0);                                      \
       /* page pg+1 is in B; request the table entry of pg+3, then pg+2 -> A */ \
       id_nxt = pt[min(pg + 3, pglast)];                                       \
       LOAD(kA, vA, id_n2)                                                     \
       __builtin_amdgcn_sched_barrier(0);                                      \
-      ATT_PAGE_ANY(kB, vB, pg + 1)                                            \
+      ATT_PAGE(kB, vB, pg + 1)                                            \
       __builtin_amdgcn_sched_barrier(0);                                      \
+    }                                                                         \
+  }
+
+// The same loop three pages deep (buffers A-C; two pages in flight while one is consumed), used
+// with the 8-bit cache: its pages are half as large, and one of them in flight per wave no longer
+// covers the memory latency.
+#define ATT_PAGE_LOOP3(LOAD)                                                  \
+  if (pg0 < pg1) {                                                            \
+    int i0 = pt[pg0], i1 = pt[min(pg0 + 1, pglast)], i2 = pt[min(pg0 + 2, pglast)]; \
+    LOAD(kA, vA, i0)                                                          \
+    LOAD(kB, vB, i1)                                                          \
+    for (int pg = pg0; pg < pg1; pg += 3) {                                   \
+      const int j0 = pt[min(pg + 3, pglast)], j1 = pt[min(pg + 4, pglast)];   \
+      const int j2 = pt[min(pg + 5, pglast)];                                 \
+      LOAD(kC, vC, i2)                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      ATT_PAGE(kA, vA, pg)                                                \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      LOAD(kA, vA, j0)                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      ATT_PAGE(kB, vB, pg + 1)                                            \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      LOAD(kB, vB, j1)                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      ATT_PAGE(kC, vC, pg + 2)                                            \
+      __builtin_amdgcn_sched_barrier(0);                                      \
+      i2 = j2;                                                                \
     }                                                                         \
   }
 
@@ -440,10 +471,19 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(
   const size_t head_off = (size_t)kvh * BLK + lane * 16;
   u32x4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
   // a wave whose share of the pages starts behind the trajectory's shared leading pages streams
-  if (pg0 >= (it.gather >> 8)) {
-    ATT_PAGE_LOOP(ATT_LOAD_STREAM)
+  if constexpr (FP8) {
+    u32x4 kC[NLD], vC[NLD];
+    if (pg0 >= (it.gather >> 8)) {
+      ATT_PAGE_LOOP3(ATT_LOAD_STREAM)
+    } else {
+      ATT_PAGE_LOOP3(ATT_LOAD_PLAIN)
+    }
   } else {
-    ATT_PAGE_LOOP(ATT_LOAD_PLAIN)
+    if (pg0 >= (it.gather >> 8)) {
+      ATT_PAGE_LOOP(ATT_LOAD_STREAM)
+    } else {
+      ATT_PAGE_LOOP(ATT_LOAD_PLAIN)
+    }
   }
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
