@@ -75,3 +75,30 @@ def test_relative_error_bound():
     x = rng.normal(0, 3, 50000)
     x = x[np.abs(x) >= 2.0 ** -6]
     assert (np.abs(e4m3_round(x) - x) / np.abs(x)).max() <= 2.0 ** -4
+
+
+def test_cache_rule_in_the_decoder_is_consistent_and_moderate():
+    # with the 8-bit cache rule the incremental decoder still equals the full forward (both see the
+    # same stored keys / values), appends in chunks equal one append, and the logits move by about
+    # the format's step relative to the unquantised model, not more
+    from oracle import OracleEngine
+    from oracle.decoder import OracleModel, forward_full
+    from synthetic import SHAPES
+    from synthetic.weights import make_weight_blob
+    shape = SHAPES["tiny"]
+    blob = make_weight_blob(shape, seed=4, weight_std=0.05, gain_std=0.1)
+    toks = np.random.default_rng(0).integers(0, shape.vocab, 41)
+    e1 = OracleEngine(blob, max_context=64, max_trajectories=2, kv_pool_pages=16, kv_cache_dtype="fp8_e4m3")
+    e1.append_observation([0], toks, [41])
+    e2 = OracleEngine(blob, max_context=64, max_trajectories=2, kv_pool_pages=16, kv_cache_dtype="fp8_e4m3")
+    e2.append_observation([0], toks[:17], [17])
+    e2.append_observation([0], toks[17:], [24])
+    z1, z2 = e1.debug_logits(0), e2.debug_logits(0)
+    assert np.abs(z1 - z2).max() < 1e-12
+    full = forward_full(e1.model, toks)[-1]
+    assert np.abs(full - z1).max() < 1e-12
+    plain = forward_full(OracleModel(blob), toks)[-1]
+    d = np.abs(plain - z1).max()
+    assert 1e-5 < d < 0.25 * plain.std()
+    with pytest.raises(ValueError):
+        OracleEngine(blob, kv_cache_dtype="int4")
