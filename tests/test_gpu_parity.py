@@ -435,7 +435,8 @@ def test_batch_composition_does_not_change_ids():
         assert [int(x) for x in ids] == [solo[i][s] for i in order]
 
 
-def test_full_size_cfg3_launch_configuration_sampled_trajectory():
+@pytest.mark.parametrize("kv", [None, "fp8_e4m3"])
+def test_full_size_cfg3_launch_configuration_sampled_trajectory(kv):
     """Qwen3-4B shape, 128 trajectories in 16 forked groups (the launch configuration bench.py
     times: same batch rows, GEMM split plan and attention grid), contexts short enough that the
     oracle can follow ONE trajectory (a forked group member) token by token.  The oracle samples
@@ -444,8 +445,9 @@ def test_full_size_cfg3_launch_configuration_sampled_trajectory():
     blob = make_weight_blob(shape, seed=1)
     n_traj, group, prompt, obs = 128, 8, 80, 24
     check = 9                                       # member 1 of group 1
-    g = rl.RolloutEngine(blob, max_context=256, max_trajectories=n_traj, kv_pool_pages=n_traj * 10)
-    o = OracleEngine(blob, max_context=256, max_trajectories=2, kv_pool_pages=32)
+    g = rl.RolloutEngine(blob, max_context=256, max_trajectories=n_traj, kv_pool_pages=n_traj * 10,
+                         flags=rl.FLAG_FP8_KV_CACHE if kv else 0)      # kv: the 8-bit cache variant
+    o = OracleEngine(blob, max_context=256, max_trajectories=2, kv_pool_pages=32, kv_cache_dtype=kv)
     rng = np.random.default_rng(2)
     leaders = np.arange(0, n_traj, group, dtype=np.int32)
     prompts = rng.integers(0, shape.vocab, (len(leaders), prompt), dtype=np.int32)
