@@ -242,18 +242,22 @@ def test_decode_step_with_appends_overflow_and_errors():
 
 @pytest.mark.parametrize("name,flags,rows,seed", [("small-d128", 0, 128, 1), ("small-d128", 2, 0, 2),
                                                  ("small-g2", 2, 256, 3), ("tiny", 0, 0, 4),
-                                                 ("tiny-bf16", 0, 128, 5)])
+                                                 ("tiny-bf16", 0, 128, 5), ("small-d128", 4, 128, 6),
+                                                 ("small-g8", 6, 0, 7)])
 def test_random_call_sequences(name, flags, rows, seed):
     # random interleavings of every entry point (append, decode, Update+Generate in one pass, fork,
     # release, log-prob recompute) on both engines: integer state identical after every call,
     # log-probs / logits within tolerance.  Small row budgets force multi-pass prefill and the
-    # fallback of the mixed pass; flag 2 = shared-prefix decode attention.
+    # fallback of the mixed pass; flag 2 = shared-prefix decode attention, flag 4 = 8-bit cache
+    # (oracle with the same cache rule; tolerance from the error model's figure for these shapes).
     shape = SHAPES[name]
     tol = TOL_FP32 if shape.weight_dtype == 0 else TOL_BF16
+    if flags & 4:
+        tol = 8.0 * 0.018
     blob = make_weight_blob(shape, seed=20 + seed, weight_std=0.03, gain_std=0.1)
     max_ctx, max_traj = 448, 8
     kw = dict(max_context=max_ctx, max_trajectories=max_traj, kv_pool_pages=max_traj * (max_ctx // 16 + 1))
-    o = OracleEngine(blob, **kw)
+    o = OracleEngine(blob, kv_cache_dtype="fp8_e4m3" if flags & 4 else None, **kw)
     g = rl.RolloutEngine(blob, flags=flags, max_batch_rows=rows, **kw)
     rng = np.random.default_rng(seed)
     length, next_id = {}, 0
