@@ -50,13 +50,18 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 // HBM into registers, D chunks ahead.  blockIdx.z selects a K-slice (split-K); every slice
 // stores its own fp32 partial sum, which the consumer kernel adds in a fixed order (no atomics:
 // results are bit-reproducible).
+// MB = number of 32-row blocks of the tile that can hold rows (1, 2 or 4; the launcher picks the
+// smallest that covers M when there is one row tile): only those blocks of the A chunk are
+// fetched, staged and multiplied.  At decode sizes a workgroup's time follows the bytes its CU
+// fetches, and the A chunk is half of them, so small batches gain most of what they leave out
+// (rows <= 32: gate-up 30.7 -> 23.6 us, down 18.3 -> 13.0 us); results per row are unchanged.
 // EPI_LSE (lm-head of the masked log-prob pass): the product is formed transposed (weights as the
 // MFMA row operand; both operands have the same lane layout, so swapping them costs nothing), which
 // puts 16 vocabulary entries of one batch row into the registers of a lane.  The epilogue reduces
 // its 32-column strip per row to (max, sum of 2^((z - max) c)) and picks out the target token's
 // logit; the logits themselves are never stored.
 // =============================================================================================
-template <int EPI, int D, int NW>
+template <int EPI, int D, int NW, int MB>
 __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ Wp,
                                                             void* __restrict__ Cv, int M, int N,
@@ -64,7 +69,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
                                                             const int32_t* __restrict__ tgt,
                                                             float* __restrict__ zt, float scale_c) {
   constexpr int NT = 64 * NW;        // threads
-  constexpr int APT = 1024 / NT;     // 16-byte pieces of an A chunk per thread
+  constexpr int APT = 256 * MB / NT; // 16-byte pieces of the used part of an A chunk per thread
   __shared__ u32x4 As[2][1024];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int nb = blockIdx.x * NW + wave;
@@ -74,11 +79,14 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
   const int c0 = blockIdx.z * chunks_per_split;
   const int c1 = min(c0 + chunks_per_split, nchunks);
   const u32x4* Ag = (const u32x4*)(A + (size_t)mt * K * 128);       // tile: 128 rows x K
+  // piece p of the used part of a chunk -> its offset in the chunk (k-block, row block, lane):
+  // with MB < 4 only the first MB row blocks of every k-block are staged
+  auto a_piece = [](int p) { return MB == 4 ? p : (p / (64 * MB)) * 256 + (p % (64 * MB)); };
   const int NB = N >> 5;
   const u32x4* Wg = (const u32x4*)Wp + (size_t)(active ? nb : 0) * 256;   // cell (chunk 0, strip nb)
-  f32x16 acc[4];
+  f32x16 acc[MB];
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+  for (int i = 0; i < MB; i++)
 #pragma unroll
     for (int j = 0; j < 16; j++) acc[i][j] = 0.f;
   // D chunks of A (for the whole workgroup) and of this wave's weight strip are kept in flight.
@@ -91,7 +99,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
   {                                                                         \
     const int cl_ = min((CHUNK), clast);                                    \
     _Pragma("unroll") for (int i = 0; i < APT; i++)                         \
-      AR[i] = Ag[(size_t)cl_ * 1024 + i * NT + tid];                        \
+      AR[i] = Ag[(size_t)cl_ * 1024 + a_piece(i * NT + tid)];               \
     _Pragma("unroll") for (int i = 0; i < 4; i++)                           \
       BR[i] = Wg[((size_t)cl_ * NB * 4 + i) * 64 + lane];                   \
     /* keep the scheduler from sinking these loads towards their use */     \
@@ -105,7 +113,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
        the masked copy also frees the staging registers before they are refilled */ \
     const unsigned keep = cc < c1 ? 0xffffffffu : 0u;                       \
     u32x4 bcur[4];                                                          \
-    _Pragma("unroll") for (int i = 0; i < APT; i++) buf[i * NT + tid] = AR[i]; \
+    _Pragma("unroll") for (int i = 0; i < APT; i++) buf[a_piece(i * NT + tid)] = AR[i]; \
     _Pragma("unroll") for (int i = 0; i < 4; i++) bcur[i] = BR[i] & keep;   \
     __builtin_amdgcn_sched_barrier(0);                                      \
     __syncthreads();                                                        \
@@ -113,11 +121,11 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
     /* all 16 row operands of the chunk are requested from LDS before the first MFMA: with one \
        wave per SIMD nothing else hides the LDS latency */                  \
     u32x4 av[16];                                                           \
-    _Pragma("unroll") for (int i = 0; i < 16; i++) av[i] = buf[i * 64 + lane]; \
+    _Pragma("unroll") for (int i = 0; i < 16; i++) if ((i & 3) < MB) av[i] = buf[i * 64 + lane]; \
     __builtin_amdgcn_sched_barrier(0);                                      \
     _Pragma("unroll") for (int kk = 0; kk < 4; kk++) {                      \
       bf16x8 b = __builtin_bit_cast(bf16x8, bcur[kk]);                      \
-      _Pragma("unroll") for (int mb = 0; mb < 4; mb++) {                    \
+      _Pragma("unroll") for (int mb = 0; mb < MB; mb++) {                   \
         bf16x8 a = __builtin_bit_cast(bf16x8, av[kk * 4 + mb]);             \
         acc[mb] = EPI == EPI_LSE                                            \
                       ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[mb], 0, 0, 0) \
@@ -144,7 +152,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
     // acc[mb][i] = z[batch row mb*32 + lane%32][vocab nb*32 + (i/4)*8 + (lane/32)*4 + i%4]
     float2* P = (float2*)Cv;
 #pragma unroll
-    for (int mb = 0; mb < 4; mb++) {
+    for (int mb = 0; mb < MB; mb++) {
       const int row = mt * 128 + mb * 32 + (lane & 31);
       float mx = acc[mb][0];
 #pragma unroll
@@ -171,7 +179,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
   const int col = nb * 32 + (lane & 31);
   float* Cp = (float*)Cv + (size_t)blockIdx.z * M * N;
 #pragma unroll
-  for (int mb = 0; mb < 4; mb++) {
+  for (int mb = 0; mb < MB; mb++) {
 #pragma unroll
     for (int i = 0; i < 16; i++) {
       int row = mt * 128 + mb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
@@ -190,13 +198,13 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
   }
 }
 
-template <int D, int NW>
+template <int D, int NW, int MB>
 static void gemm_launch(hipStream_t s, dim3 grid, const bf16_t* A, const bf16_t* Wp, void* C, int M,
                         int N, int K, int epilogue, int cps) {
   if (epilogue == EPI_STORE)
-    gemm_mfma_kernel<EPI_STORE, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps, nullptr, nullptr, 0.f);
+    gemm_mfma_kernel<EPI_STORE, D, NW, MB><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps, nullptr, nullptr, 0.f);
   else
-    gemm_mfma_kernel<EPI_SWIGLU, D, NW><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps, nullptr, nullptr, 0.f);
+    gemm_mfma_kernel<EPI_SWIGLU, D, NW, MB><<<grid, 64 * NW, 0, s>>>(A, Wp, C, M, N, K, cps, nullptr, nullptr, 0.f);
 }
 
 // depth = chunks in flight per workgroup (2 or 4)
@@ -209,10 +217,20 @@ int launch_gemm_mfma_cfg(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void*
   int cps = (nchunks + splits - 1) / splits;
   splits = (nchunks + cps - 1) / cps;
   dim3 grid((N + 32 * nw - 1) / (32 * nw), (M + 127) / 128, splits);
-  if (nw == 2 && depth == 2) gemm_launch<2, 2>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
-  else if (nw == 2) gemm_launch<4, 2>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
-  else if (depth == 2) gemm_launch<2, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
-  else gemm_launch<4, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  const int mb = M <= 32 ? 1 : M <= 64 ? 2 : 4;    // row blocks in use (one row tile when < 4)
+  if (nw == 2 && depth == 2) {
+    if (mb == 1) gemm_launch<2, 2, 1>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+    else if (mb == 2) gemm_launch<2, 2, 2>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+    else gemm_launch<2, 2, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  } else if (nw == 2) {
+    gemm_launch<4, 2, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  } else if (depth == 2) {
+    if (mb == 1) gemm_launch<2, 4, 1>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+    else if (mb == 2) gemm_launch<2, 4, 2>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+    else gemm_launch<2, 4, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  } else {
+    gemm_launch<4, 4, 4>(s, grid, A, Wp, C, M, N, K, epilogue, cps);
+  }
   return splits;
 }
 
@@ -255,7 +273,7 @@ void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, in
                             const int32_t* tgt, float scale_c, float* part, float* zt, float* lp) {
   if (M <= 0) return;
   dim3 grid((V + 127) / 128, (M + 127) / 128, 1);
-  gemm_mfma_kernel<EPI_LSE, 2, 4><<<grid, 256, 0, s>>>(A, Wp, part, M, V, K, K / 64, tgt, zt, scale_c);
+  gemm_mfma_kernel<EPI_LSE, 2, 4, 4><<<grid, 256, 0, s>>>(A, Wp, part, M, V, K, K / 64, tgt, zt, scale_c);
   lse_finish_kernel<<<M, 256, 0, s>>>((const float2*)part, zt, V / 32, scale_c, lp);
 }
 
