@@ -69,10 +69,10 @@ def decode_step_table(fetch_path, write_path):
         return copy_bytes / (best * 1024.0) if best else float("nan")
 
     kf, kw = calib(fetch), calib(write)
-    expect = {("gemm_mfma_kernel<0, 2, 4>", 240 * 256): "QKV: 31.5 MB weights + 5 x 3.1 MB partial sums written",
-              ("gemm_mfma_kernel<0, 2, 4>", 160 * 256): "O / down mixed: 35.4 MB weights + 8 x 1.3 MB written",
-              ("gemm_mfma_kernel<2, 2, 4>", 152 * 256): "gate-up: 99.6 MB weights, 2.5 MB written",
-              ("gemm_mfma_kernel<0, 2, 4>", 1187 * 256): "lm-head: 777.9 MB weights, 77.8 MB logits written"}
+    expect = {("gemm_mfma_kernel<0, 2, 4, 4>", 240 * 256): "QKV: 31.5 MB weights + 5 x 3.1 MB partial sums written",
+              ("gemm_mfma_kernel<0, 2, 4, 4>", 160 * 256): "O / down mixed: 35.4 MB weights + 8 x 1.3 MB written",
+              ("gemm_mfma_kernel<2, 2, 4, 4>", 152 * 256): "gate-up: 99.6 MB weights, 2.5 MB written",
+              ("gemm_mfma_kernel<0, 2, 4, 4>", 1187 * 256): "lm-head: 777.9 MB weights, 77.8 MB logits written"}
     print("# HBM traffic per dispatch of the decode-step kernels (Qwen3-4B shape, 128 trajectories)\n")
     print("Commands (MI355X box, repository root; one counter per run; the rollout is shortened, the "
           "decode launch shapes are those of the full workload):\n")
