@@ -442,7 +442,7 @@ __device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
 }
 
 template <bool FP8>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void attention_mfma_kernel(
     const bf16_t* __restrict__ q, const char* __restrict__ kpool, const char* __restrict__ vpool,
     const AttnItem* __restrict__ items, const int32_t* __restrict__ rowlist,
     const int32_t* __restrict__ page_table, bf16_t* __restrict__ o, float* __restrict__ scratch,
