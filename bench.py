@@ -38,7 +38,7 @@ def recorded_traffic(config):
     """HBM bytes per decode-attention launch from the committed rocprofv3 counter summary, or None
     when there is none for this workload or the kernel source changed since it was taken."""
     import re
-    from bench_counters import kernel_source_hash
+    from paper_2509_06980_amd.profile_summary import kernel_source_hash
     path = os.path.join(ROOT, "profiles", f"attention_mfma_{config}_hbm_counters.md")
     try:
         txt = open(path).read()
@@ -103,21 +103,31 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
             for i in ev[1]:
                 tot += ctx[int(i)]
                 ctx[int(i)] += 1
-            # algorithmic bytes of this decode step: weights once, every cached key/value once,
-            # one new key/value row per trajectory
-            nbytes = wbytes + (tot + len(ev[1])) * kvtok
+            # algorithmic bytes of this decode step: weights once, every cached key/value of a
+            # DISTINCT page once (the engine counts a page that a forked group shares once per
+            # step), one new key/value row per trajectory.  The count that charges every
+            # trajectory its whole context is kept beside it under its own name.
+            nbytes_traj = wbytes + (tot + len(ev[1])) * kvtok
+            kv_b, kv_u, acc_n = engine.timing_read_decode_bytes(reset=True)
+            if acc_n == 1:
+                nbytes = wbytes + kv_u * shape.n_layers + len(ev[1]) * kvtok
+            else:       # accounting off (warm-up) or a step that also carried appended rows
+                nbytes = nbytes_traj
+                stats["decode_steps_without_page_accounting"] = stats.get("decode_steps_without_page_accounting", 0) + 1
             stats["decode_bytes"] += nbytes
+            stats["decode_bytes_per_trajectory"] = stats.get("decode_bytes_per_trajectory", 0.0) + nbytes_traj
             stats["decode_steps"] += 1
             n_gen += len(ev[1])
             # the same figures per run of consecutive decode steps (one generation turn)
             turns = stats.setdefault("turns", [])
             if not turns or turns[-1]["closed"]:
-                turns.append(dict(closed=False, steps=0, s=0.0, bytes=0.0, tokens=0,
+                turns.append(dict(closed=False, steps=0, s=0.0, bytes=0.0, bytes_traj=0.0, tokens=0,
                                   ctx_first=tot / len(ev[1]), ctx_last=0.0))
             tr = turns[-1]
             tr["steps"] += 1
             tr["s"] += dt
             tr["bytes"] += nbytes
+            tr["bytes_traj"] += nbytes_traj
             tr["tokens"] += len(ev[1])
             tr["ctx_last"] = tot / len(ev[1])
         elif kind == "release":
@@ -199,29 +209,68 @@ def tool_loop_bench(rl, blob, shape, args):
     return res
 
 
-def cpu_baseline(blob, shape, budget_note):
-    """Time the CPU oracle (as is) on a small slice of the same workload."""
+def cpu_baseline_and_parity(blob, shape, rl):
+    """The CPU oracle (as it stands) on a slice of the workload, and the GPU engine against it.
+
+    Slice: n_traj trajectories holding a `prompt`-token context each at the benchmark's model shape.
+    The oracle's prompt prefill is outside the timed region.  Timed: one decode step of all
+    trajectories with every host core the numerical library uses, then one decode step of one
+    trajectory limited to one thread.  The same calls go to a GPU engine (teacher-forced with the
+    oracle's ids): `parity` holds the distances this run measured at this shape, next to what
+    rounding to bf16 alone does on the same trajectory (oracle/bf16_error_model.py)."""
     from oracle import OracleEngine
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    big = shape.linear_params() > 1e9
-    n_traj, prompt, steps = (2, 32, 2) if big else ((4, 64, 4) if shape.linear_params() > 1e8 else (4, 32, 16))
+    from oracle.bf16_error_model import forward_bf16_model
+    from threadpoolctl import threadpool_info, threadpool_limits
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    n_traj, prompt = (4, 512) if shape.linear_params() > 1e8 else (4, 32)
     rng = np.random.default_rng(2)
     toks = rng.integers(0, shape.vocab, n_traj * prompt, dtype=np.int32)
     ids = np.arange(n_traj, dtype=np.int32)
+    lens = np.full(n_traj, prompt, np.int32)
+    kw = dict(max_context=prompt + 16, max_trajectories=n_traj, kv_pool_pages=n_traj * (prompt // 16 + 2))
+    o = OracleEngine(blob, **kw)
+    g = rl.RolloutEngine(blob, **kw)
     t0 = time.perf_counter()
-    o = OracleEngine(blob, max_context=prompt + steps + 1, max_trajectories=n_traj,
-                     kv_pool_pages=n_traj * ((prompt + steps) // 16 + 2))
-    o.append_observation(ids, toks, np.full(n_traj, prompt, np.int32))
-    for _ in range(steps):
-        o.decode_step(ids, 1.0, 3)
-    dt = time.perf_counter() - t0
-    return {"value": n_traj * steps / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n_traj} trajectories x ({prompt}-token prompt prefill + {steps} sampled tokens) "
-                      f"at the same model shape, float64 numpy oracle, {dt:.1f} s wall; {budget_note}"}
+    o.append_observation(ids, toks, lens)
+    g.append_observation(ids, toks, lens)
+    zo = np.stack([o.debug_logits(int(i)) for i in ids])        # runs the oracle's prefill
+    t_prefill = time.perf_counter() - t0
+    zg = np.stack([g.debug_logits(int(i)) for i in ids])
+    print(f"[bench] oracle prefill of {n_traj} x {prompt} tokens: {t_prefill:.1f}s (untimed)", file=sys.stderr, flush=True)
+    t0 = time.perf_counter()
+    tok, lp = o.decode_step(ids, 1.0, 3)
+    dt_all = time.perf_counter() - t0
+    glp = g.decode_step_forced(ids, 1.0, tok)
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        o.decode_step(ids[:1], 1.0, 3)
+        dt_one = time.perf_counter() - t0
+    print(f"[bench] oracle decode step: {dt_all:.1f}s for {n_traj} tokens on {cores} threads, "
+          f"{dt_one:.1f}s for 1 token on one thread", file=sys.stderr, flush=True)
+    zm = forward_bf16_model(o.model, toks[:prompt])[-1]
+    g.close()
+    err, merr = zg - zo, zm - zo[0]
+    dlp = float(np.abs(glp - lp).max())
+    base = {"value": n_traj / dt_all, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "single_thread_value": 1.0 / dt_one,
+            "sample": f"slice, not the full workload: one decode step of {n_traj} trajectories at context "
+                      f"{prompt} at the same model shape, float64 numpy oracle as it stands ({dt_all:.1f} s on "
+                      f"{cores} threads; single_thread_value: one trajectory, one thread, {dt_one:.1f} s); the "
+                      f"oracle's prompt prefill ({t_prefill:.1f} s) is outside the timed region; baseline only, "
+                      "not the target"}
+    parity = {"shape_rows_context": [n_traj, prompt], "dtype": "bf16" if shape.weight_dtype == 1 else "f32",
+              "max_abs_dlogit": round(float(np.abs(err).max()), 5),
+              "rms_dlogit": round(float(np.sqrt((err ** 2).mean())), 5),
+              "max_abs_dlogp": round(dlp, 5),
+              "bf16_rounding_model_rms_dlogit": round(float(np.sqrt((merr ** 2).mean())), 5),
+              "bf16_rounding_model_max_abs_dlogit": round(float(np.abs(merr).max()), 5),
+              "logit_std": round(float(zo.std()), 4),
+              "bound_3e-2_met_here": bool(np.abs(err).max() < 3e-2 and dlp < 3e-2),
+              "note": "GPU engine vs the float64 oracle on the slice the CPU baseline runs, this run; the "
+                      "3e-2 bound is asserted by the GPU tests at the 2-3 layer shapes; at this depth "
+                      "rounding activations and cache to bf16 alone gives the bf16_rounding_model figures, "
+                      "and the tests hold the GPU to that model"}
+    return base, parity
 
 
 def main():
@@ -331,7 +380,11 @@ def main():
                             "frac": round(stats["decode_bytes"] / stats["decode_s"] / 1e9 / HBM_PEAK_GBS, 4),
                             "frac_of_measured_stream_read":
                                 round(stats["decode_bytes"] / stats["decode_s"] / 1e9 / stream_gbs, 4),
-                            "note": "algorithmic bytes of all decode steps / wall time inside rl_decode_step"}
+                            "achieved_counting_shared_pages_per_trajectory":
+                                round(stats.get("decode_bytes_per_trajectory", 0.0) / stats["decode_s"] / 1e9, 1),
+                            "note": "algorithmic bytes of all decode steps (weights once, keys/values of the "
+                                    "distinct pages of each step once: a prompt page shared by a forked group "
+                                    "counts once) / wall time inside rl_decode_step"}
         if stats["decode_s"] else None,
         "recompute": {"tokens_per_s": round(stats["recompute_tokens"] / stats["recompute_s"], 1),
                       "tokens": stats["recompute_tokens"], "seconds": round(stats["recompute_s"], 3),
@@ -348,7 +401,8 @@ def main():
              "decode_steps": t["steps"], "tokens_per_s": round(t["tokens"] / t["s"], 1),
              "ms_per_decode_step": round(t["s"] * 1e3 / t["steps"], 3),
              "hbm_GBs": round(t["bytes"] / t["s"] / 1e9, 1),
-             "hbm_frac": round(t["bytes"] / t["s"] / 1e9 / HBM_PEAK_GBS, 4)}
+             "hbm_frac": round(t["bytes"] / t["s"] / 1e9 / HBM_PEAK_GBS, 4),
+             "hbm_GBs_counting_shared_pages_per_trajectory": round(t["bytes_traj"] / t["s"] / 1e9, 1)}
             for t in stats.get("turns", [])],
         "append_mfma": append_mfma(stats, shape),
         "append_s_per_step": round(stats["append_s"] / max(args.steps, 1), 3),
@@ -359,7 +413,8 @@ def main():
         eng.close()
         out["tool_loop"] = tool_loop_bench(rl, blob, shape, args)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(blob, shape, "baseline only, not the target")
+        eng.close()
+        out["cpu_baseline"], out["parity"] = cpu_baseline_and_parity(blob, shape, rl)
     print(json.dumps(out), flush=True)
 
 

@@ -59,7 +59,9 @@ typedef struct {
   int32_t page_tokens;      /* tokens per KV page; must be 16 */
   int32_t max_context;      /* longest trajectory, in tokens */
   int32_t max_trajectories; /* live trajectories at any time */
-  int64_t kv_pool_pages;    /* pages in the pool (each holds page_tokens tokens of every layer) */
+  int64_t kv_pool_pages;    /* pages in the pool (each holds page_tokens tokens of every layer);
+                               0: sized automatically: max_trajectories x ceil(max_context / 16),
+                               capped by 85 % of the device memory free at load time */
   int32_t max_batch_rows;   /* rows processed per internal pass of an append (0: default 8192) */
   int32_t flags;            /* RL_FLAG_* */
 } rl_runtime_config;
@@ -84,6 +86,7 @@ typedef struct {
  * embed[V,H]; per layer g_in[H] W_q W_k W_v g_q[d] g_k[d] W_o g_post[H] W_gate W_up W_down;
  * g_final[H]; lm_head[V,H] unless tied), copy and repack the weights into device memory,
  * build the RoPE table and allocate the KV page pool.  `weights` may be freed on return.
+ * head_dim must be even and at most 128.
  * Errors: RL_E_ARG (bad header / size / config), RL_E_HIP (allocation).
  */
 int rl_model_load(const rl_runtime_config* rt, const void* weights, size_t nbytes,
@@ -219,6 +222,13 @@ uint32_t rl_uniform_u32(uint64_t seed, int32_t traj_id, int32_t position);
 int rl_timing_enable(rl_model* m, int32_t every);
 int rl_timing_read(rl_model* m, double* attn_ms, int64_t* attn_launches, double* attn_kv_bytes,
                    double* attn_kv_unique_bytes, int reset);
+/* Byte accounting of the decode steps (Generate step, Section 2.3.2) made while timing is enabled
+ * (every step, not only the timed ones; steps that also carried appended rows are left out): keys +
+ * values of one layer that the steps' attention had to read, summed over the steps.  kv_bytes
+ * counts every trajectory's context; kv_unique_bytes counts a page that several trajectories of a
+ * step share (a forked prompt) once per step.  Multiply by the layer count for a whole step. */
+int rl_timing_read_decode_bytes(rl_model* m, double* kv_bytes, double* kv_unique_bytes,
+                                int64_t* steps, int reset);
 /* GPU time of the timed decode steps, first kernel to sampler (HIP events), and their count. */
 int rl_timing_read_steps(rl_model* m, double* step_gpu_ms, int64_t* steps, int reset);
 

@@ -11,7 +11,7 @@ EXPORTED_SYMBOLS = [
     "rl_append_observation", "rl_decode_step", "rl_release", "rl_fork", "rl_traj_info",
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
     "rl_decode_step_forced", "rl_sample_from_logits", "rl_uniform_u32", "rl_timing_enable",
-    "rl_timing_read", "rl_timing_read_steps", "rl_measure_stream_read",
+    "rl_timing_read", "rl_timing_read_steps", "rl_timing_read_decode_bytes", "rl_measure_stream_read",
     "rl_decode_step_with_appends", "rl_decode_step_forced_with_appends", "rl_grpo_objective",
 ]
 
@@ -86,6 +86,8 @@ def load_library():
     lib.rl_timing_read.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int]
     lib.rl_timing_read_steps.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    lib.rl_timing_read_decode_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                                C.POINTER(C.c_int64), C.c_int]
     lib.rl_measure_stream_read.argtypes = [C.c_size_t, C.c_int32, C.POINTER(C.c_double)]
     _lib = lib
     return lib
@@ -293,3 +295,10 @@ class RolloutEngine:
         ms, n = C.c_double(), C.c_int64()
         _check(self._lib.rl_timing_read_steps(self._h, C.byref(ms), C.byref(n), int(reset)))
         return ms.value, n.value
+
+    def timing_read_decode_bytes(self, reset=True):
+        """(kv bytes per trajectory, kv bytes of distinct pages, steps): one layer, summed over the
+        decode steps accounted since the last reset."""
+        b, u, n = C.c_double(), C.c_double(), C.c_int64()
+        _check(self._lib.rl_timing_read_decode_bytes(self._h, C.byref(b), C.byref(u), C.byref(n), int(reset)))
+        return b.value, u.value, n.value

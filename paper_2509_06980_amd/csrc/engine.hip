@@ -101,7 +101,9 @@ struct rl_model {
   double attn_ms = 0.0, attn_bytes = 0.0, attn_unique_bytes = 0.0, step_gpu_ms = 0.0, step_wall_ms = 0.0;
   int64_t steps_timed = 0;
   hipEvent_t ev_step[2] = {nullptr, nullptr};
-  std::vector<uint32_t> page_stamp;   // per page: last timed step that counted it
+  double acct_kv_bytes = 0.0, acct_kv_unique_bytes = 0.0;   // per layer, summed over accounted decode steps
+  int64_t acct_steps = 0;
+  std::vector<uint32_t> page_stamp;   // per page: last accounted step that counted it
   uint32_t stamp = 0;
   std::vector<hipEvent_t> ev;
 
@@ -201,15 +203,9 @@ void forward_generic(rl_model* m, int M, const RowMeta& r) {
 // costs M x N floats of traffic; 8 measured best in the full decode step).  Prefill-sized GEMMs already have many row tiles.
 struct GemmPlan { int nw, splits; };
 const int kMaxSplits = 8;
-int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  return v && *v ? atoi(v) : dflt;
-}
 // part_rows: rows the partial-sum buffers hold (every split-K slice takes M of them)
 GemmPlan plan_gemm(int M, int N, int K, bool can_split, size_t part_rows) {
-  // tuning overrides (development): RL_GEMM_TARGET_WGS, RL_GEMM_MAX_SPLITS
-  static const int target = env_int("RL_GEMM_TARGET_WGS", 240);
-  static const int max_splits = std::min(kMaxSplits, env_int("RL_GEMM_MAX_SPLITS", kMaxSplits));
+  const int target = 240, max_splits = kMaxSplits;
   int tiles = ((N + 127) / 128) * ((M + 127) / 128);
   int s = 1;
   if (can_split && M <= 1024 && tiles < target) {   // decode steps, mixed steps and small appends
@@ -637,20 +633,6 @@ int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, u
   bool timed = extra_rows == 0 && m->timing_every > 0 && (m->decode_steps % m->timing_every) == 0;
   m->decode_steps++;
   double kvu = 0.0;
-  if (timed) {   // bytes of distinct pages: pages shared by forked trajectories count once
-    if (m->page_stamp.size() != m->refcount.size()) m->page_stamp.assign(m->refcount.size(), 0);
-    m->stamp++;
-    double tokb = 2.0 * m->md.nkv * m->md.d * m->kv_el;
-    for (Traj* t : ts) {
-      int nt = (int)t->tokens.size();
-      for (int pg = 0; pg * RL_PAGE < nt; pg++) {
-        int page = t->pages[pg];
-        if (m->page_stamp[page] == m->stamp) continue;
-        m->page_stamp[page] = m->stamp;
-        kvu += tokb * std::min(RL_PAGE, nt - pg * RL_PAGE);
-      }
-    }
-  }
   RowMeta r{dm.tok, dm.pos, dm.slot, dm.items, n_dec_items, dm.merges, (int)st.merges.size(),
             dm.rowlist, dm.items + n_dec_items, (int)st.items.size() - n_dec_items, false, kvb, timed};
   if (timed) (void)hipEventRecord(m->ev_step[0], m->stream);
@@ -664,6 +646,25 @@ int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, u
   if (timed) (void)hipEventRecord(m->ev_step[1], m->stream);
   HIPCHECK(hipMemcpyAsync(m->h_ids, m->d_ids, n * 4, hipMemcpyDeviceToHost, m->stream));
   HIPCHECK(hipMemcpyAsync(m->h_lp, m->d_lp, n * 4, hipMemcpyDeviceToHost, m->stream));
+  if (m->timing_every > 0 && extra_rows == 0) {
+    // byte accounting of pure decode steps, done while the GPU works: keys + values per trajectory,
+    // and of the distinct pages (pages shared by forked trajectories count once)
+    if (m->page_stamp.size() != m->refcount.size()) m->page_stamp.assign(m->refcount.size(), 0);
+    m->stamp++;
+    const double tokb = 2.0 * m->md.nkv * m->md.d * m->kv_el;
+    for (Traj* t : ts) {
+      const int nt = (int)t->tokens.size();
+      for (int pg = 0; pg * RL_PAGE < nt; pg++) {
+        const int page = t->pages[pg];
+        if (m->page_stamp[page] == m->stamp) continue;
+        m->page_stamp[page] = m->stamp;
+        kvu += tokb * std::min(RL_PAGE, nt - pg * RL_PAGE);
+      }
+    }
+    m->acct_kv_bytes += kvb;
+    m->acct_kv_unique_bytes += kvu;
+    m->acct_steps++;
+  }
   HIPCHECK(hipStreamSynchronize(m->stream));
   if (timed) {
     float sms = 0.f;
@@ -721,12 +722,13 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   memcpy(&c, b + 8, sizeof(c));
   if (c.n_layers <= 0 || c.hidden <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 ||
       c.intermediate <= 0 || c.vocab <= 0 || c.n_q_heads % c.n_kv_heads != 0 || c.head_dim % 2 != 0 ||
-      c.head_dim > 256 || (c.weight_dtype != 0 && c.weight_dtype != 1))
+      (c.weight_dtype != 0 && c.weight_dtype != 1))
     return fail(RL_E_ARG, "bad model config");
+  if (c.head_dim > 128) return fail(RL_E_ARG, "head_dim above 128 is not supported");
   if (c.weight_dtype == 1 && (c.hidden % 16 != 0 || c.intermediate % 16 != 0))
     return fail(RL_E_ARG, "bf16 models need hidden and intermediate to be multiples of 16");
   if (rt->page_tokens != RL_PAGE || rt->max_context <= 0 || rt->max_trajectories <= 0 ||
-      rt->kv_pool_pages <= 0 || rt->kv_pool_pages > 0x7fffffff || rt->max_batch_rows < 0)
+      rt->kv_pool_pages < 0 || rt->kv_pool_pages > 0x7fffffff || rt->max_batch_rows < 0)
     return fail(RL_E_ARG, "bad runtime config");
   BlobMap bm = map_blob(c);
   size_t el = c.weight_dtype == 1 ? 2 : 4;
@@ -824,15 +826,31 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   }
   // ---- KV pool ----
   m->page_bytes = (size_t)c.n_kv_heads * RL_PAGE * d * m->kv_el;
+  if (m->rt.kv_pool_pages == 0) {
+    // automatic size: a page for every token of every trajectory at max_context, capped by 85 % of
+    // the device memory that is free now (the work buffers below come out of the rest)
+    size_t free_b = 0, total_b = 0;
+    HIPTRY(hipMemGetInfo(&free_b, &total_b));
+    const double per_page = 2.0 * (double)m->page_bytes * c.n_layers;
+    const int64_t want = (int64_t)rt->max_trajectories * max_pages;
+    const int64_t fit = (int64_t)(0.85 * (double)free_b / per_page);
+    m->rt.kv_pool_pages = std::min<int64_t>(std::min(want, fit), 0x7fffffff);
+    if (m->rt.kv_pool_pages <= 0) {
+      fail(RL_E_HIP, "no device memory left for the KV page pool");
+      rl_model_free(m);
+      return RL_E_HIP;
+    }
+  }
+  const int64_t pool_pages = m->rt.kv_pool_pages;
   m->pools.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; l++) {
-    TRY(m->dalloc(&m->pools[l].k, m->page_bytes * rt->kv_pool_pages, true));
-    TRY(m->dalloc(&m->pools[l].v, m->page_bytes * rt->kv_pool_pages, true));
+    TRY(m->dalloc(&m->pools[l].k, m->page_bytes * pool_pages, true));
+    TRY(m->dalloc(&m->pools[l].v, m->page_bytes * pool_pages, true));
   }
   TRY(m->dalloc((void**)&m->page_table, (size_t)rt->max_trajectories * max_pages * 4, true));
-  m->refcount.assign(rt->kv_pool_pages, 0);
-  for (int p = 0; p < rt->kv_pool_pages; p++) m->free_pages.push(p);
-  m->n_free = rt->kv_pool_pages;
+  m->refcount.assign(pool_pages, 0);
+  for (int p = 0; p < pool_pages; p++) m->free_pages.push(p);
+  m->n_free = pool_pages;
   for (int s = rt->max_trajectories - 1; s >= 0; s--) m->free_slots.push_back(s);
   // ---- work buffers ----
   m->Mcap = round_up(std::max(m->rt.max_batch_rows, rt->max_trajectories), 128);
@@ -1434,6 +1452,16 @@ extern "C" int rl_timing_read_steps(rl_model* m, double* step_gpu_ms, int64_t* s
   if (step_gpu_ms) *step_gpu_ms = m->step_gpu_ms;
   if (steps) *steps = m->steps_timed;
   if (reset) { m->step_gpu_ms = 0.0; m->steps_timed = 0; }
+  return RL_OK;
+}
+
+extern "C" int rl_timing_read_decode_bytes(rl_model* m, double* kv_bytes, double* kv_unique_bytes,
+                                           int64_t* steps, int reset) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  if (kv_bytes) *kv_bytes = m->acct_kv_bytes;
+  if (kv_unique_bytes) *kv_unique_bytes = m->acct_kv_unique_bytes;
+  if (steps) *steps = m->acct_steps;
+  if (reset) { m->acct_kv_bytes = 0.0; m->acct_kv_unique_bytes = 0.0; m->acct_steps = 0; }
   return RL_OK;
 }
 

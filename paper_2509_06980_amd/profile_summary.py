@@ -2,7 +2,7 @@
 """Summarise rocprofv3 counter runs of bench.py for the decode-attention kernel.
 
 Usage (after the two counter runs named in the summary it writes):
-    python bench_counters.py FETCH.csv WRITE.csv [STATS.csv] > profiles/<name>.md
+    python -m paper_2509_06980_amd.profile_summary FETCH.csv WRITE.csv [STATS.csv] > profiles/<name>.md
 
 FETCH.csv / WRITE.csv are rocprofv3 `--pmc FETCH_SIZE` / `--pmc WRITE_SIZE` counter_collection
 files (KiB per dispatch).  Both counters are calibrated against the largest device-to-device
@@ -16,8 +16,8 @@ import os
 import sys
 from collections import defaultdict
 
-ROOT = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SRC = os.path.join(ROOT, "paper_2509_06980_amd", "csrc", "kernels_mfma.hip")
+HERE = os.path.dirname(os.path.abspath(__file__))
+KERNEL_SRC = os.path.join(HERE, "csrc", "kernels_mfma.hip")
 
 
 def kernel_source_hash():
@@ -80,7 +80,7 @@ def decode_step_table(fetch_path, write_path):
           "--warmup 0 --no-cpu-baseline --scale 0.1")
     print("    rocprofv3 --pmc WRITE_SIZE --output-format csv -d out/pmc_write_all -o w -- python3 bench.py "
           "--warmup 0 --no-cpu-baseline --scale 0.1")
-    print("    python bench_counters.py --decode-step <f_counter_collection.csv> <w_counter_collection.csv>\n")
+    print("    python -m paper_2509_06980_amd.profile_summary --decode-step <f_counter_collection.csv> <w_counter_collection.csv>\n")
     print(f"FETCH_SIZE factor {kf:.4f}, WRITE_SIZE factor {kw:.4f} (embedding-table copy of {copy_bytes} bytes).\n")
     print("| kernel | grid (threads) | dispatches | fetched MB | written MB | algorithmic |\n|---|---|---|---|---|---|")
     rows = []
@@ -122,7 +122,7 @@ def main():
           "--output-format csv -d out/pmc_fetch -o f -- python3 bench.py --warmup 0 --no-cpu-baseline")
     print("    rocprofv3 --pmc WRITE_SIZE --kernel-include-regex 'attention_mfma_kernel|copyBuffer' "
           "--output-format csv -d out/pmc_write -o w -- python3 bench.py --warmup 0 --no-cpu-baseline")
-    print("    python bench_counters.py <f_counter_collection.csv> <w_counter_collection.csv>\n")
+    print("    python -m paper_2509_06980_amd.profile_summary <f_counter_collection.csv> <w_counter_collection.csv>\n")
     print(f"Calibration copy: embedding table, {copy_bytes} bytes read and written by `__amd_rocclr_copyBuffer`; "
           f"FETCH_SIZE factor {kf:.4f}, WRITE_SIZE factor {kw:.4f} (expected bytes / counter KiB x 1024).\n")
     print(f"Decode launches (grid {grid} threads): {len(fa)} with FETCH_SIZE, {len(wa)} with WRITE_SIZE.\n")
