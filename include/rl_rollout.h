@@ -209,6 +209,24 @@ int rl_decode_step_forced_with_appends(rl_model* m, const int32_t* app_traj_ids,
  * uniform per row.  Same arithmetic as inside rl_decode_step. */
 int rl_sample_from_logits(const float* logits, int32_t rows, int32_t vocab, float temperature,
                           const uint32_t* u32, int32_t* ids_out, float* logprobs_out);
+/*
+ * rl_sample_from_logits for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Unlike every other call here the
+ * pointers are DEVICE pointers (`rows` rows of `vocab` float32 logits, row stride `vocab`; one
+ * uniform per row; outputs ids and log-probs); `stream` is a hipStream_t (NULL: the default stream).
+ * The kernels are enqueued on `stream` and the call returns without waiting for them.  It calls no
+ * hipMalloc / hipFree: the per-segment scratch of the sampler is a fixed array inside the library's
+ * device image (384 KiB per GPU, held until the process ends) that holds rows x ceil(vocab / 4096)
+ * <= 16384 segments; larger requests fail with RL_E_ARG and launch nothing.  All calls on one GPU
+ * share that array: calls that overlap in time on one GPU (different streams or threads) race.
+ * Nothing in the array has to be cleared between calls.  The address of the array is looked up
+ * once per GPU, by rl_model_load or by the first call on that GPU; make that first call outside
+ * graph capture.  Same arithmetic and results as rl_sample_from_logits.
+ * Errors: ARG, HIP.
+ */
+int rl_sample_device_logits(const float* d_logits, int32_t rows, int32_t vocab, float temperature,
+                            const uint32_t* d_u32, int32_t* d_ids_out, float* d_logprobs_out,
+                            void* stream);
 /* SplitMix64 output number ((traj_id << 32) | position) + 1 from state `seed`, top 32 bits. */
 uint32_t rl_uniform_u32(uint64_t seed, int32_t traj_id, int32_t position);
 

@@ -10,7 +10,7 @@ EXPORTED_SYMBOLS = [
     "rl_model_load", "rl_model_free", "rl_model_get_config", "rl_last_error",
     "rl_append_observation", "rl_decode_step", "rl_release", "rl_fork", "rl_traj_info",
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
-    "rl_decode_step_forced", "rl_sample_from_logits", "rl_uniform_u32", "rl_timing_enable",
+    "rl_decode_step_forced", "rl_sample_from_logits", "rl_sample_device_logits", "rl_uniform_u32", "rl_timing_enable",
     "rl_timing_read", "rl_timing_read_steps", "rl_timing_read_decode_bytes", "rl_measure_stream_read",
     "rl_decode_step_with_appends", "rl_decode_step_forced_with_appends", "rl_grpo_objective",
 ]
@@ -80,6 +80,8 @@ def load_library():
                                       C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     lib.rl_debug_logits.argtypes = [C.c_void_p, C.c_int32, _F32P]
     lib.rl_sample_from_logits.argtypes = [_F32P, C.c_int32, C.c_int32, C.c_float, _U32P, _I32P, _F32P]
+    lib.rl_sample_device_logits.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p]
     lib.rl_uniform_u32.argtypes = [C.c_uint64, C.c_int32, C.c_int32]
     lib.rl_uniform_u32.restype = C.c_uint32
     lib.rl_timing_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -127,6 +129,14 @@ def sample_from_logits(logits, temperature, u32):
         z.ctypes.data_as(_F32P), z.shape[0], z.shape[1], float(temperature),
         u.ctypes.data_as(_U32P), ids.ctypes.data_as(_I32P), lps.ctypes.data_as(_F32P)))
     return ids, lps
+
+
+def sample_device_logits(d_logits, rows, vocab, temperature, d_u32, d_ids_out, d_logprobs_out, stream=0):
+    """rl_sample_device_logits: all buffers are device addresses (integers); enqueues on `stream` (a
+    hipStream_t as an integer, 0 = default stream) and returns without synchronising."""
+    _check(load_library().rl_sample_device_logits(
+        C.c_void_p(int(d_logits)), int(rows), int(vocab), float(temperature), C.c_void_p(int(d_u32)),
+        C.c_void_p(int(d_ids_out)), C.c_void_p(int(d_logprobs_out)), C.c_void_p(int(stream))))
 
 
 class RolloutEngine:

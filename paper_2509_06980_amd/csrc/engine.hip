@@ -24,6 +24,7 @@ static int fail(int code, const std::string& msg) {
   return code;
 }
 extern "C" const char* rl_last_error(void) { return g_err.c_str(); }
+int rl_fail(int code, const char* msg) { return fail(code, msg ? msg : ""); }
 
 #define HIPCHECK(expr)                                                                      \
   do {                                                                                      \
@@ -757,6 +758,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
 #define TRY(x) do { rc = (x); if (rc) { rl_model_free(m); return rc; } } while (0)
 #define HIPTRY(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fail(RL_E_HIP, std::string(#x) + ": " + hipGetErrorString(e_)); rl_model_free(m); return RL_E_HIP; } } while (0)
   HIPTRY(hipStreamCreate(&m->stream));
+  HIPTRY((hipError_t)sampler_noalloc_prepare());
   // ---- weights ----
   int H = c.hidden, d = c.head_dim, I = c.intermediate, V = c.vocab;
   int qw = c.n_q_heads * d, kvw = c.n_kv_heads * d;

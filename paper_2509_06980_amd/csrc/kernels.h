@@ -135,6 +135,13 @@ void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, in
                     const int32_t* row_newpos, const int32_t* forced, const uint8_t* out_mask,
                     SamplerScratch sc, int32_t* ids_out, float* logp_out);
 
+// Sets the thread's rl_last_error() message and returns `code` (defined beside the C boundary).
+int rl_fail(int code, const char* msg);
+// Looks up the current device's copy of the sampler's fixed scratch array (used by the entry point
+// that allocates nothing); 0 or a hipError_t.  Model load calls it so that the lookup has happened
+// before a caller's first sampling call.
+int sampler_noalloc_prepare();
+
 // Masked GRPO objective (forward value).  advantages: adv[i] of trajectory i within its group of G
 // consecutive rewards, (r - mean) / (std + eps_std), std with divisor G - ddof; also clears the 3 n
 // accumulators acc.  terms: for every row k of segment (traj, k0, k1) with use[k] != 0 adds

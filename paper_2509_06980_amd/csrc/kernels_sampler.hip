@@ -11,6 +11,7 @@
 //
 // Three launches over segments of RL_SAMPLER_SEG logits: per-segment max, per-segment weight sums,
 // then one workgroup per row locates the segment and the token inside it.
+#include "../../include/rl_rollout.h"
 #include "kernels.h"
 
 #pragma clang fp contract(off)
@@ -206,4 +207,65 @@ void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, in
   sample_final_kernel<<<rows, 256, 0, s>>>(logits, ldz, V, scale_c, greedy, nseg, sc.segmax,
                                            sc.segarg, sc.segw, sc.sege, u32, seed, row_traj,
                                            row_newpos, forced, out_mask, ids_out, logp_out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The sampler for callers that must not allocate device memory.  Its per-segment scratch lives in
+// a fixed array in the library's device image; every GPU holds its own copy at its own address,
+// looked up once per device.  Host code uses that address only, never the array's name.
+// ---------------------------------------------------------------------------------------------
+#define RL_NOALLOC_MAX_SEGMENTS 16384   // rows x ceil(vocab / RL_SAMPLER_SEG) of one call
+#define RL_NOALLOC_SEG_BYTES 24         // max 4 + arg 4 + weight 8 + sum 4, padded to keep 8-byte alignment
+static __device__ __align__(256) unsigned char scratch[(size_t)RL_NOALLOC_MAX_SEGMENTS * RL_NOALLOC_SEG_BYTES];
+
+#define RL_MAX_DEVICES 64
+static unsigned char* g_scratch_ptr[RL_MAX_DEVICES];   // per device: address of its copy of `scratch`
+
+// Address of the current device's scratch array (looked up on first use), or null with *err set.
+static unsigned char* noalloc_scratch(hipError_t* err) {
+  int dev = 0;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= RL_MAX_DEVICES) { *err = hipErrorInvalidDevice; return nullptr; }
+  if (!g_scratch_ptr[dev]) {
+    unsigned char* p = nullptr;
+    *err = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
+int sampler_noalloc_prepare() {
+  hipError_t e;
+  return noalloc_scratch(&e) ? 0 : (int)e;
+}
+
+extern "C" int rl_sample_device_logits(const float* d_logits, int32_t rows, int32_t vocab,
+                                       float temperature, const uint32_t* d_u32, int32_t* d_ids_out,
+                                       float* d_logprobs_out, void* stream) {
+  if (!d_logits || !d_u32 || !d_ids_out || !d_logprobs_out || rows <= 0 || vocab <= 0 ||
+      !(temperature >= 0.0f))
+    return rl_fail(RL_E_ARG, "bad argument");
+  const int nseg = sampler_nseg(vocab);
+  const size_t seg_n = (size_t)rows * nseg;
+  if (seg_n > RL_NOALLOC_MAX_SEGMENTS)
+    return rl_fail(RL_E_ARG, "rows x ceil(vocab / 4096) exceeds the 16384 segments of the fixed scratch");
+  hipError_t e;
+  unsigned char* base = noalloc_scratch(&e);
+  if (!base) return rl_fail(RL_E_HIP, hipGetErrorString(e));
+  // every entry the final kernel reads is written by the two segment kernels of this call first:
+  // nothing has to start at zero
+  SamplerScratch sc;
+  sc.segw = (uint64_t*)base;
+  sc.segmax = (float*)(sc.segw + seg_n);
+  sc.segarg = (int32_t*)(sc.segmax + seg_n);
+  sc.sege = (float*)(sc.segarg + seg_n);
+  const bool greedy = temperature == 0.0f;
+  const float c = (float)(1.4426950408889634 / (greedy ? 1.0 : (double)temperature));
+  launch_sampler((hipStream_t)stream, d_logits, (size_t)vocab, rows, vocab, c, greedy ? 1 : 0, d_u32, 0,
+                 nullptr, nullptr, nullptr, nullptr, sc, d_ids_out, d_logprobs_out);
+  e = hipGetLastError();
+  if (e != hipSuccess) return rl_fail(RL_E_HIP, hipGetErrorString(e));
+  return RL_OK;
 }
