@@ -84,6 +84,7 @@ struct rl_model {
   SamplerScratch ss{};
   int32_t *d_ids = nullptr, *h_ids = nullptr;
   float *d_lp = nullptr, *h_lp = nullptr;
+  float* d_stripmax = nullptr;   // [Rl, V / 32] maxima of 32-logit strips from the lm-head epilogue
   float *d_zt = nullptr, *d_lp_rows = nullptr, *h_lp_rows = nullptr;   // masked log-prob pass: Mcap rows
   uint8_t* d_mask = nullptr;
   // objective pass: per-row old / reference log-probs, use flags and segments (device + pinned
@@ -261,7 +262,9 @@ void forward_rows(rl_model* m, int M, const RowMeta& r) {
 
 // final norm + lm-head for rows [r0, r0 + R) of m->h -> m->logits[0 .. R)
 // M: rows of the forward pass (stride of its partial sums); norm_rows <= M: leading rows to normalise
-void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done, int norm_rows = -1) {
+// stripmax (MFMA path only): also leave the per-strip maxima of the logits there
+void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done, int norm_rows = -1,
+                  float* stripmax = nullptr) {
   hipStream_t s = m->stream;
   const ModelDims& md = m->md;
   if (norm_rows < 0) norm_rows = M;
@@ -272,9 +275,14 @@ void lm_head_rows(rl_model* m, int M, int r0, int R, bool norm_done, int norm_ro
       m->pending_parts = 0;
     }
     // r0 is a multiple of 128: skip whole A tiles
-    GemmPlan pl = plan_gemm(R, md.V, md.H, false, m->part_rows);
-    launch_gemm_mfma(s, (const bf16_t*)m->xa + (size_t)r0 * md.H, (const bf16_t*)m->lm_head, m->logits,
-                     R, md.V, md.H, EPI_STORE, 1, pl.nw);
+    if (stripmax) {
+      launch_lm_head_logits(s, (const bf16_t*)m->xa + (size_t)r0 * md.H, (const bf16_t*)m->lm_head,
+                            m->logits, R, md.V, md.H, stripmax);
+    } else {
+      GemmPlan pl = plan_gemm(R, md.V, md.H, false, m->part_rows);
+      launch_gemm_mfma(s, (const bf16_t*)m->xa + (size_t)r0 * md.H, (const bf16_t*)m->lm_head, m->logits,
+                       R, md.V, md.H, EPI_STORE, 1, pl.nw);
+    }
   } else if (m->bf16) {
     if (!norm_done)
       launch_rmsnorm<bf16_t, bf16_t>(s, m->h, (const bf16_t*)m->g_final, (bf16_t*)m->xa, norm_rows, md.H, md.eps, false);
@@ -638,11 +646,16 @@ int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, u
             dm.rowlist, dm.items + n_dec_items, (int)st.items.size() - n_dec_items, false, kvb, timed};
   if (timed) (void)hipEventRecord(m->ev_step[0], m->stream);
   forward_rows(m, M, r);
-  lm_head_rows(m, M, 0, n, false, n);
   bool greedy = temperature == 0.0f;
+  // sampling needs the row maximum before any weight can be formed: the lm-head epilogue leaves the
+  // maximum of every 32-logit strip, so no separate pass over the logits looks for it (the arg-max
+  // of a greedy step still takes that pass)
+  float* stripmax = (m->mfma && !greedy) ? m->d_stripmax : nullptr;
+  lm_head_rows(m, M, 0, n, false, n, stripmax);
   float c = (float)(1.4426950408889634 / (greedy ? 1.0 : (double)temperature));
   launch_sampler(m->stream, m->logits, (size_t)m->md.V, n, m->md.V, c, greedy ? 1 : 0, nullptr, seed,
-                 dm.traj, dm.newpos, forced ? dm.forced : nullptr, nullptr, m->ss, m->d_ids, m->d_lp);
+                 dm.traj, dm.newpos, forced ? dm.forced : nullptr, nullptr, m->ss, m->d_ids, m->d_lp,
+                 stripmax, m->md.V / 32);
   HIPCHECK(hipGetLastError());
   if (timed) (void)hipEventRecord(m->ev_step[1], m->stream);
   HIPCHECK(hipMemcpyAsync(m->h_ids, m->d_ids, n * 4, hipMemcpyDeviceToHost, m->stream));
@@ -882,6 +895,7 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc((void**)&m->ss.segarg, (size_t)m->Rl * nseg * 4));
   TRY(m->dalloc((void**)&m->ss.segw, (size_t)m->Rl * nseg * 8));
   TRY(m->dalloc((void**)&m->ss.sege, (size_t)m->Rl * nseg * 4));
+  if (m->mfma) TRY(m->dalloc((void**)&m->d_stripmax, (size_t)m->Rl * (V / 32) * 4));
   TRY(m->dalloc((void**)&m->d_ids, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_lp, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_mask, Mc));

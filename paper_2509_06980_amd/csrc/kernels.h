@@ -84,7 +84,7 @@ template <typename TA>
 void launch_swiglu(hipStream_t s, const float* gu, TA* m, int M, int I, bool atile);
 
 // ---- MFMA kernels (bf16, head_dim 128) -------------------------------------------------------
-enum GemmEpilogue { EPI_STORE = 0, EPI_SWIGLU = 2, EPI_LSE = 3 };
+enum GemmEpilogue { EPI_STORE = 0, EPI_SWIGLU = 2, EPI_LSE = 3, EPI_STORE_MAX = 4 };
 // A: bf16 A-tile layout [ceil(M/128)*128, K]; Wp: repacked weights (see repack kernel).
 // EPI_STORE: split-K slice z writes its fp32 partial sum to C + z * M * N (row-major [M, N]); the
 // consumer adds the `splits` partials.  EPI_SWIGLU (splits = 1): C is bf16 A-tile [.., N/2], gate
@@ -97,6 +97,11 @@ int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, 
 // stored) and scale_c = log2(e) / T.  part: scratch of M * (V / 32) float pairs; zt: M floats.
 void launch_lm_head_logprob(hipStream_t s, const bf16_t* A, const bf16_t* Wp, int M, int V, int K,
                             const int32_t* tgt, float scale_c, float* part, float* zt, float* lp);
+// lm-head of a decode step (final norm -> lm-head -> sampler): logits[M, V] fp32 row-major and, from
+// the same epilogue, stripmax[M, V / 32]: the maximum of every 32 consecutive logits of a row, from
+// which the sampler takes the row maximum without a pass over the logits.  V % 32 == 0.
+void launch_lm_head_logits(hipStream_t s, const bf16_t* A, const bf16_t* Wp, float* logits, int M,
+                           int V, int K, float* stripmax);
 // W[N,K] row-major -> operand strips.  interleave16: rows come from two matrices Wg, Wu
 // ([N/2,K] each) interleaved in groups of 16 (gate, up, gate, up, ...).
 void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16_t* Wp, int N,
@@ -130,10 +135,13 @@ static inline int sampler_nseg(int V) { return (V + RL_SAMPLER_SEG - 1) / RL_SAM
 //  u32 != null: use these draws; else draw from (seed, row_traj[r], row_newpos[r]).
 //  forced != null: id = forced[r] (no draw).  out_mask != null: logprob forced to 0 where
 //  out_mask[r] != 0.
+//  stripmax != null (not with greedy): [rows, nstrips] maxima that together cover each row (from
+//  the lm-head epilogue); the pass over the logits that finds the row maximum is then left out.
 void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, int V, float scale_c,
                     int greedy, const uint32_t* u32, uint64_t seed, const int32_t* row_traj,
                     const int32_t* row_newpos, const int32_t* forced, const uint8_t* out_mask,
-                    SamplerScratch sc, int32_t* ids_out, float* logp_out);
+                    SamplerScratch sc, int32_t* ids_out, float* logp_out,
+                    const float* stripmax = nullptr, int nstrips = 0);
 
 // Sets the thread's rl_last_error() message and returns `code` (defined beside the C boundary).
 int rl_fail(int code, const char* msg);

@@ -60,6 +60,10 @@ void launch_repack_weight(hipStream_t s, const bf16_t* W, const bf16_t* Wu, bf16
 // puts 16 vocabulary entries of one batch row into the registers of a lane.  The epilogue reduces
 // its 32-column strip per row to (max, sum of 2^((z - max) c)) and picks out the target token's
 // logit; the logits themselves are never stored.
+// EPI_STORE_MAX (lm-head of a decode step): EPI_STORE plus, per row, the maximum over the wave's 32
+// columns (a butterfly over the 32 lanes of each half that halves the values a lane holds at every
+// step), written to zt[row * (N / 32) + strip]: the sampler gets the row maximum it needs before
+// any weight can be formed from V / 32 numbers per row instead of a pass over the logits.
 // =============================================================================================
 template <int EPI, int D, int NW, int MB>
 __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __restrict__ A,
@@ -178,6 +182,45 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
   }
   const int col = nb * 32 + (lane & 31);
   float* Cp = (float*)Cv + (size_t)blockIdx.z * M * N;
+  if (EPI == EPI_STORE_MAX) {
+    // v[j], j = 16 mb + i, is the value of row mt*128 + 32 mb + (i>>2)*8 + (lane>>5)*4 + (i&3) in
+    // this lane's column.  Step s pairs lanes L and L ^ (1 << s): of every two values the lane
+    // with bit s clear keeps the even one, the other lane the odd one, and each takes the maximum
+    // with what its partner held of the kept one.  After the five steps lane L holds the strip
+    // maxima of the values j = 32 k + (L & 31).
+    float v[16 * MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+      for (int i = 0; i < 16; i++) v[mb * 16 + i] = acc[mb][i];
+    int n = 16 * MB;
+#pragma unroll
+    for (int st = 0; st < 5; st++) {
+      const bool up = (lane >> st) & 1;
+      if (n >= 2) {
+        n >>= 1;
+#pragma unroll
+        for (int k = 0; k < 32; k++)
+          if (k < n) {
+            const float keep = up ? v[2 * k + 1] : v[2 * k];
+            const float send = up ? v[2 * k] : v[2 * k + 1];
+            v[k] = fmaxf(keep, __shfl_xor(send, 1 << st, 64));
+          }
+      } else {
+        v[0] = fmaxf(v[0], __shfl_xor(v[0], 1 << st, 64));
+      }
+    }
+    constexpr int NOUT = MB == 4 ? 2 : 1;
+    const int jl = MB == 1 ? (lane & 15) : (lane & 31);
+    if (MB > 1 || (lane & 16) == 0) {
+#pragma unroll
+      for (int k = 0; k < NOUT; k++) {
+        const int j = 32 * k + jl, mb = j >> 4, i = j & 15;
+        const int row = mt * 128 + mb * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+        if (row < M) zt[(size_t)row * NB + nb] = v[k];
+      }
+    }
+  }
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) {
 #pragma unroll
@@ -238,6 +281,20 @@ int launch_gemm_mfma(hipStream_t s, const bf16_t* A, const bf16_t* Wp, void* C, 
                      int K, int epilogue, int splits, int nw) {
   // two chunks in flight: fewer registers, more resident workgroups (measured best at M = 128)
   return launch_gemm_mfma_cfg(s, A, Wp, C, M, N, K, epilogue, splits, nw, 2);
+}
+
+// lm-head of a decode step: logits[M, V] (fp32, row-major) and stripmax[M, V / 32].
+void launch_lm_head_logits(hipStream_t s, const bf16_t* A, const bf16_t* Wp, float* logits, int M,
+                           int V, int K, float* stripmax) {
+  if (M <= 0) return;
+  dim3 grid((V + 127) / 128, (M + 127) / 128, 1);
+  const int cps = K / 64;
+  if (M <= 32)
+    gemm_mfma_kernel<EPI_STORE_MAX, 2, 4, 1><<<grid, 256, 0, s>>>(A, Wp, logits, M, V, K, cps, nullptr, stripmax, 0.f);
+  else if (M <= 64)
+    gemm_mfma_kernel<EPI_STORE_MAX, 2, 4, 2><<<grid, 256, 0, s>>>(A, Wp, logits, M, V, K, cps, nullptr, stripmax, 0.f);
+  else
+    gemm_mfma_kernel<EPI_STORE_MAX, 2, 4, 4><<<grid, 256, 0, s>>>(A, Wp, logits, M, V, K, cps, nullptr, stripmax, 0.f);
 }
 
 // One workgroup per row: combine the per-strip (max, sum) pairs in a fixed order and write

@@ -82,16 +82,34 @@ __global__ void seg_max_kernel(const float* __restrict__ z, size_t ldz, int V,
   }
 }
 
-// grid (nseg, rows), block 256
+// Row maximum from n partial maxima (all 256 threads of the block call it; the maximum does not
+// depend on the order, so every kernel that forms it this way gets the same bits).
+__device__ __forceinline__ float block_max_of(const float* __restrict__ p, int n) {
+  __shared__ float red[4];
+  float m = -INFINITY;
+  for (int j = threadIdx.x; j < n; j += 256) m = fmaxf(m, p[j]);
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  return m;
+}
+
+// grid (nseg, rows), block 256.  The row maximum comes from the per-segment maxima of
+// seg_max_kernel or, when the lm-head epilogue has left per-strip maxima, from those.
 __global__ void seg_weight_kernel(const float* __restrict__ z, size_t ldz, int V, float c,
                                   const float* __restrict__ segmax, uint64_t* __restrict__ segw,
-                                  float* __restrict__ sege) {
+                                  float* __restrict__ sege, const float* __restrict__ stripmax,
+                                  int nstrips) {
   __shared__ uint64_t sw[4];
   __shared__ float se[4];
   int seg = blockIdx.x, row = blockIdx.y, nseg = gridDim.x;
   const float* zr = z + (size_t)row * ldz;
   float m = -INFINITY;
-  for (int k = 0; k < nseg; k++) m = fmaxf(m, segmax[(size_t)row * nseg + k]);
+  if (stripmax) m = block_max_of(stripmax + (size_t)row * nstrips, nstrips);
+  else
+    for (int k = 0; k < nseg; k++) m = fmaxf(m, segmax[(size_t)row * nseg + k]);
   uint64_t ws = 0;
   float es = 0.f;
   for (int i = 0; i < RL_SAMPLER_SEG / 256; i++) {
@@ -126,7 +144,8 @@ __global__ void sample_final_kernel(const float* __restrict__ z, size_t ldz, int
                                     const int32_t* __restrict__ row_newpos,
                                     const int32_t* __restrict__ forced,
                                     const uint8_t* __restrict__ out_mask,
-                                    int32_t* __restrict__ ids_out, float* __restrict__ logp_out) {
+                                    int32_t* __restrict__ ids_out, float* __restrict__ logp_out,
+                                    const float* __restrict__ stripmax, int nstrips) {
   __shared__ uint64_t tsum[256];
   __shared__ int chosen;
   int row = blockIdx.x, tid = threadIdx.x;
@@ -135,9 +154,12 @@ __global__ void sample_final_kernel(const float* __restrict__ z, size_t ldz, int
   int arg = 0;
   uint64_t W = 0;
   float E = 0.f;
+  if (stripmax) m = block_max_of(stripmax + (size_t)row * nstrips, nstrips);
   for (int k = 0; k < nseg; k++) {
-    float v = segmax[(size_t)row * nseg + k];
-    if (v > m) { m = v; arg = segarg[(size_t)row * nseg + k]; }   // first segment wins ties
+    if (!stripmax) {
+      float v = segmax[(size_t)row * nseg + k];
+      if (v > m) { m = v; arg = segarg[(size_t)row * nseg + k]; }   // first segment wins ties
+    }
     W += segw[(size_t)row * nseg + k];
     E = __fadd_rn(E, sege[(size_t)row * nseg + k]);
   }
@@ -198,15 +220,19 @@ __global__ void sample_final_kernel(const float* __restrict__ z, size_t ldz, int
 void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, int V, float scale_c,
                     int greedy, const uint32_t* u32, uint64_t seed, const int32_t* row_traj,
                     const int32_t* row_newpos, const int32_t* forced, const uint8_t* out_mask,
-                    SamplerScratch sc, int32_t* ids_out, float* logp_out) {
+                    SamplerScratch sc, int32_t* ids_out, float* logp_out, const float* stripmax,
+                    int nstrips) {
   if (rows <= 0) return;
   int nseg = sampler_nseg(V);
   dim3 grid(nseg, rows);
-  seg_max_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, sc.segmax, sc.segarg);
-  seg_weight_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, scale_c, sc.segmax, sc.segw, sc.sege);
+  if (greedy || nstrips <= 0) stripmax = nullptr;   // the arg-max needs the pass over the logits
+  if (!stripmax) seg_max_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, sc.segmax, sc.segarg);
+  seg_weight_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, scale_c, sc.segmax, sc.segw, sc.sege,
+                                         stripmax, nstrips);
   sample_final_kernel<<<rows, 256, 0, s>>>(logits, ldz, V, scale_c, greedy, nseg, sc.segmax,
                                            sc.segarg, sc.segw, sc.sege, u32, seed, row_traj,
-                                           row_newpos, forced, out_mask, ids_out, logp_out);
+                                           row_newpos, forced, out_mask, ids_out, logp_out,
+                                           stripmax, nstrips);
 }
 
 // ---------------------------------------------------------------------------------------------
