@@ -117,6 +117,10 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
             stats["decode_bytes"] += nbytes
             stats["decode_bytes_per_trajectory"] = stats.get("decode_bytes_per_trajectory", 0.0) + nbytes_traj
             stats["decode_steps"] += 1
+            if stats["decode_steps"] % 512 == 0:     # progress of the work itself
+                print(f"[bench] {stats['decode_steps']} decode steps, mean context {tot / len(ev[1]):.0f}, "
+                      f"{stats['decode_s']:.1f}s in decode, {stats['append_s']:.1f}s in appends",
+                      file=sys.stderr, flush=True)
             n_gen += len(ev[1])
             # the same figures per run of consecutive decode steps (one generation turn)
             turns = stats.setdefault("turns", [])
@@ -137,9 +141,11 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
     if ctx:   # workload without a final release (cfg5): recompute all log-probs, then release
         ids = np.array(sorted(ctx), np.int32)
         gen = {int(i): engine.traj_read(int(i)) for i in ids[:4]}
+        print(f"[bench] log-prob recompute over {ids.size} trajectories", file=sys.stderr, flush=True)
         t0 = time.perf_counter()
         lp = engine.recompute_logprobs(ids, 1.0)
         stats["recompute_s"] = stats.get("recompute_s", 0.0) + time.perf_counter() - t0
+        print(f"[bench] recompute done in {stats['recompute_s']:.1f}s; objective pass", file=sys.stderr, flush=True)
         stats["recompute_tokens"] = stats.get("recompute_tokens", 0) + int(lp.size)
         off, worst = 0, 0.0
         for i in ids[:4]:      # recomputed values against the log-probs returned at generation time
