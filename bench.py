@@ -147,13 +147,15 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
         stats["recompute_s"] = stats.get("recompute_s", 0.0) + time.perf_counter() - t0
         print(f"[bench] recompute done in {stats['recompute_s']:.1f}s; objective pass", file=sys.stderr, flush=True)
         stats["recompute_tokens"] = stats.get("recompute_tokens", 0) + int(lp.size)
-        off, worst = 0, 0.0
+        off, worst, checked = 0, 0.0, 0
         for i in ids[:4]:      # recomputed values against the log-probs returned at generation time
             _, mask, glp, _ = gen[int(i)]
             worst = max(worst, float(np.abs(lp[off:off + glp.size] - glp).max()))
             assert np.all(lp[off:off + glp.size][mask == 1] == 0.0)
+            checked += int((mask == 0).sum())
             off += ctx[int(i)]
         stats["recompute_max_abs_diff"] = worst
+        stats["recompute_checked"] = checked
         # masked GRPO objective over the same trajectories (seeded rewards, the recomputed log-probs
         # as reference policy): one more teacher-forced pass with the reduction on the device
         G = 8 if ids.size % 8 == 0 else 1
@@ -421,6 +423,19 @@ def main():
     if not args.no_cpu_baseline:
         eng.close()
         out["cpu_baseline"], out["parity"] = cpu_baseline_and_parity(blob, shape, rl)
+        if out["recompute"]:
+            # two GPU schedules (decode steps, teacher-forced pass), each within the rounding model's
+            # spread of the oracle: their difference over n compared tokens stays below
+            # sqrt(2) * sigma * z(n) with probability 1 - 1e-4 (z: normal quantile, as in the tests)
+            from scipy.stats import norm
+            n_chk = max(stats.get("recompute_checked", 1), 1)
+            bound = float(np.sqrt(2.0) * out["parity"]["bf16_rounding_model_rms_dlogit"] * norm.isf(1e-4 / (2.0 * n_chk)))
+            out["recompute"]["tokens_compared"] = n_chk
+            out["recompute"]["bound_from_rounding_model"] = round(bound, 5)
+            out["recompute"]["within_bound"] = bool(stats["recompute_max_abs_diff"] < bound)
+            if not out["recompute"]["within_bound"]:
+                print("[bench] WARNING: recomputed log-probs differ from the generation-time ones by more "
+                      "than the rounding model allows", file=sys.stderr, flush=True)
     print(json.dumps(out), flush=True)
 
 

@@ -22,9 +22,10 @@ def round_bf16(x):
     return u.view(np.float32).astype(np.float64)
 
 
-def forward_bf16_model(m: OracleModel, tokens, points=ALL_POINTS):
+def forward_bf16_model(m: OracleModel, tokens, points=ALL_POINTS, rows=None):
     """Logits [n, V]; `points` selects which tensors are rounded (a, b: normed inputs of the two
-    sub-blocks; q, k, v; p: probabilities; o: attention output; m: SwiGLU output; f: final norm)."""
+    sub-blocks; q, k, v; p: probabilities; o: attention output; m: SwiGLU output; f: final norm).
+    rows: only these positions' logits are formed (long sequences with a large vocabulary)."""
     r = lambda x, key: round_bf16(x) if key in points else x
     tokens = np.asarray(tokens, dtype=np.int64)
     n, d = len(tokens), m.head_dim
@@ -59,4 +60,6 @@ def forward_bf16_model(m: OracleModel, tokens, points=ALL_POINTS):
         mm = r(silu(b @ m.w(p + "w_gate").T) * (b @ m.w(p + "w_up").T), "m")
         h = h + mm @ m.w(p + "w_down").T
     f = r(rmsnorm(h, m.w("g_final"), m.rms_eps), "f")
+    if rows is not None:
+        f = f[rows]
     return f @ m.w("lm_head").T

@@ -82,34 +82,37 @@ __global__ void seg_max_kernel(const float* __restrict__ z, size_t ldz, int V,
   }
 }
 
-// Row maximum from n partial maxima (all 256 threads of the block call it; the maximum does not
-// depend on the order, so every kernel that forms it this way gets the same bits).
-__device__ __forceinline__ float block_max_of(const float* __restrict__ p, int n) {
+// grid rows, block 256: the row maximum from the per-strip maxima that the lm-head epilogue left,
+// written into every per-segment slot of the row, so that the two kernels below find it where
+// seg_max_kernel would have put the segment maxima (the maximum does not depend on the order of
+// the reduction: same bits either way).  The arg-max is not formed (sampling does not need it).
+__global__ void row_max_kernel(const float* __restrict__ stripmax, int nstrips, int nseg,
+                               float* __restrict__ segmax, int32_t* __restrict__ segarg) {
   __shared__ float red[4];
+  const int row = blockIdx.x;
+  const float* p = stripmax + (size_t)row * nstrips;
   float m = -INFINITY;
-  for (int j = threadIdx.x; j < n; j += 256) m = fmaxf(m, p[j]);
+  for (int j = threadIdx.x; j < nstrips; j += 256) m = fmaxf(m, p[j]);
   m = wave_max(m);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
   __syncthreads();
   m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  __syncthreads();
-  return m;
+  for (int k = threadIdx.x; k < nseg; k += 256) {
+    segmax[(size_t)row * nseg + k] = m;
+    segarg[(size_t)row * nseg + k] = 0;
+  }
 }
 
-// grid (nseg, rows), block 256.  The row maximum comes from the per-segment maxima of
-// seg_max_kernel or, when the lm-head epilogue has left per-strip maxima, from those.
+// grid (nseg, rows), block 256
 __global__ void seg_weight_kernel(const float* __restrict__ z, size_t ldz, int V, float c,
                                   const float* __restrict__ segmax, uint64_t* __restrict__ segw,
-                                  float* __restrict__ sege, const float* __restrict__ stripmax,
-                                  int nstrips) {
+                                  float* __restrict__ sege) {
   __shared__ uint64_t sw[4];
   __shared__ float se[4];
   int seg = blockIdx.x, row = blockIdx.y, nseg = gridDim.x;
   const float* zr = z + (size_t)row * ldz;
   float m = -INFINITY;
-  if (stripmax) m = block_max_of(stripmax + (size_t)row * nstrips, nstrips);
-  else
-    for (int k = 0; k < nseg; k++) m = fmaxf(m, segmax[(size_t)row * nseg + k]);
+  for (int k = 0; k < nseg; k++) m = fmaxf(m, segmax[(size_t)row * nseg + k]);
   uint64_t ws = 0;
   float es = 0.f;
   for (int i = 0; i < RL_SAMPLER_SEG / 256; i++) {
@@ -144,8 +147,7 @@ __global__ void sample_final_kernel(const float* __restrict__ z, size_t ldz, int
                                     const int32_t* __restrict__ row_newpos,
                                     const int32_t* __restrict__ forced,
                                     const uint8_t* __restrict__ out_mask,
-                                    int32_t* __restrict__ ids_out, float* __restrict__ logp_out,
-                                    const float* __restrict__ stripmax, int nstrips) {
+                                    int32_t* __restrict__ ids_out, float* __restrict__ logp_out) {
   __shared__ uint64_t tsum[256];
   __shared__ int chosen;
   int row = blockIdx.x, tid = threadIdx.x;
@@ -154,12 +156,9 @@ __global__ void sample_final_kernel(const float* __restrict__ z, size_t ldz, int
   int arg = 0;
   uint64_t W = 0;
   float E = 0.f;
-  if (stripmax) m = block_max_of(stripmax + (size_t)row * nstrips, nstrips);
   for (int k = 0; k < nseg; k++) {
-    if (!stripmax) {
-      float v = segmax[(size_t)row * nseg + k];
-      if (v > m) { m = v; arg = segarg[(size_t)row * nseg + k]; }   // first segment wins ties
-    }
+    float v = segmax[(size_t)row * nseg + k];
+    if (v > m) { m = v; arg = segarg[(size_t)row * nseg + k]; }   // first segment wins ties
     W += segw[(size_t)row * nseg + k];
     E = __fadd_rn(E, sege[(size_t)row * nseg + k]);
   }
@@ -226,13 +225,12 @@ void launch_sampler(hipStream_t s, const float* logits, size_t ldz, int rows, in
   int nseg = sampler_nseg(V);
   dim3 grid(nseg, rows);
   if (greedy || nstrips <= 0) stripmax = nullptr;   // the arg-max needs the pass over the logits
-  if (!stripmax) seg_max_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, sc.segmax, sc.segarg);
-  seg_weight_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, scale_c, sc.segmax, sc.segw, sc.sege,
-                                         stripmax, nstrips);
+  if (stripmax) row_max_kernel<<<rows, 256, 0, s>>>(stripmax, nstrips, nseg, sc.segmax, sc.segarg);
+  else seg_max_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, sc.segmax, sc.segarg);
+  seg_weight_kernel<<<grid, 256, 0, s>>>(logits, ldz, V, scale_c, sc.segmax, sc.segw, sc.sege);
   sample_final_kernel<<<rows, 256, 0, s>>>(logits, ldz, V, scale_c, greedy, nseg, sc.segmax,
                                            sc.segarg, sc.segw, sc.sege, u32, seed, row_traj,
-                                           row_newpos, forced, out_mask, ids_out, logp_out,
-                                           stripmax, nstrips);
+                                           row_newpos, forced, out_mask, ids_out, logp_out);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -95,9 +95,50 @@ def decode_step_table(fetch_path, write_path):
         print(f"| {k[:60]} | {g} | {n} | {fm:.2f} | {wm:.2f} | {expect.get((k, g), '')} |")
 
 
+def mfma_table(counter_path, trace_path):
+    """Matrix-core work per kernel and launch shape: bf16 MFMA operations the hardware counted
+    (SQ_INSTS_VALU_MFMA_MOPS_BF16, 512 flops each) against the kernel's duration from a kernel trace
+    of the same command, for every shape with at least 20 dispatches."""
+    mops = read_counter(counter_path, "SQ_INSTS_VALU_MFMA_MOPS_BF16")
+    dur = defaultdict(lambda: defaultdict(list))
+    with open(trace_path, newline="") as f:
+        for r in csv.DictReader(f):
+            name = r["Kernel_Name"].split("(")[0]
+            name = name[5:] if name.startswith("void ") else name
+            g = int(r.get("Grid_Size_X") or r.get("Grid_Size"))
+            dur[name][g].append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+    peak = 2500.0
+    print("# Matrix-core (MFMA) utilisation of the chunked-prefill kernels and the decode GEMMs "
+          "(Qwen3-4B shape, 128 trajectories)\n")
+    print("Commands (MI355X box, repository root; counters and durations in separate runs of the same command):\n")
+    print("    rocprofv3 --pmc SQ_INSTS_VALU_MFMA_MOPS_BF16 --kernel-include-regex 'gemm_mfma|attention' "
+          "--output-format csv -d out/pmc_mfma -o m -- python3 bench.py --warmup 0 --no-cpu-baseline --scale 0.5")
+    print("    rocprofv3 --kernel-trace --output-format csv -d out/trace_half -o t -- python3 bench.py --warmup 0 "
+          "--no-cpu-baseline --scale 0.5")
+    print("    python -m paper_2509_06980_amd.profile_summary --mfma <m_counter_collection.csv> <t_kernel_trace.csv>\n")
+    print("MFMA flops = counter x 512 (the counter includes the padded columns and rows a kernel "
+          "multiplies: decode attention fills 4 of 16 MFMA columns, a 128-row decode GEMM all of them); "
+          f"peak {peak:.0f} TFLOP/s dense bf16.\n")
+    print("| kernel | grid (threads) | dispatches | avg us | MFMA GFLOP per dispatch | TFLOP/s | of peak |\n|---|---|---|---|---|---|---|")
+    rows = []
+    for k, grids in mops.items():
+        for g, vals in grids.items():
+            d = dur.get(k, {}).get(g, [])
+            if len(vals) < 20 or not d:
+                continue
+            fl = sum(vals) / len(vals) * 512.0
+            us = sum(d) / len(d) / 1e3
+            rows.append((k, g, len(vals), us, fl))
+    for k, g, n, us, fl in sorted(rows, key=lambda r: -r[2] * r[3]):
+        tf = fl / (us * 1e-6) / 1e12 if us > 0 else 0.0
+        print(f"| {k[:64]} | {g} | {n} | {us:.1f} | {fl / 1e9:.1f} | {tf:.0f} | {tf / peak:.3f} |")
+
+
 def main():
     if sys.argv[1] == "--trace":
         return trace_summary(sys.argv[2])
+    if sys.argv[1] == "--mfma":
+        return mfma_table(sys.argv[2], sys.argv[3])
     if sys.argv[1] == "--decode-step":
         return decode_step_table(sys.argv[2], sys.argv[3])
     fetch = read_counter(sys.argv[1], "FETCH_SIZE")

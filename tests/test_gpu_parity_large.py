@@ -170,3 +170,54 @@ def test_automatic_pool_size():
     g.append_observation([0], np.arange(40), [40])
     assert g.n_free_pages() == 5 * 63 - 3
     g.close()
+
+
+def test_4b_shape_context_2048_decode_in_the_timed_launch_configuration():
+    """Qwen3-4B shape, 128 trajectories in 16 forked groups, free-running through two full turns of
+    the headline workload (512 sampled + 256 appended tokens each, 8192 rows per prefill pass) to a
+    context of 2048: 128-entry page tables, positions far above 1024, decode attention over 128
+    pages per row.  Then one trajectory's tokens go to the oracle, which prefills them and samples
+    three more tokens; the GPU decodes the whole batch teacher-forced with them.  Logits and
+    log-probs at context 2048 are held to the rounding model of this very trajectory."""
+    shape = SHAPES["qwen3-4b"]
+    blob = make_weight_blob(shape, seed=1)
+    w = uniform_turns("cfg3-two-turns", shape.vocab, 128, 512, 2, 512, 256, 1.0, group_size=8,
+                      final_release=False)
+    g = rl.RolloutEngine(blob, max_context=2304, max_trajectories=128, kv_pool_pages=128 * 146)
+    for ev in w.events:
+        if ev[0] == "append":
+            g.append_observation(ev[1], ev[2], ev[3])
+        elif ev[0] == "fork":
+            g.fork(ev[1], ev[2])
+        elif ev[0] == "decode":
+            g.decode_step(ev[1], ev[2], ev[3])
+    check = 43                                   # member 3 of group 5
+    toks, mask, gen_lp, pages = g.traj_read(check)
+    assert len(toks) == 2048 and len(pages) == 128 and int((mask == 0).sum()) == 1024
+    assert list(pages[:31]) == list(g.traj_read(40)[3][:31])      # 511 prompt tokens: 31 whole shared pages
+    o = OracleEngine(blob, max_context=2304, max_trajectories=1, kv_pool_pages=160)
+    o.append_observation([check], toks, [len(toks)])
+    zo = o.debug_logits(check)                   # the oracle's prefill of 2048 tokens
+    zg = g.debug_logits(check)                   # one row alone: its context is cut into parts and merged
+    ids = np.arange(128, dtype=np.int32)
+    rng = np.random.default_rng(3)
+    dlp = []
+    for step in range(3):
+        tok, lp = o.decode_step([check], 1.0, 3)
+        forced = rng.integers(0, shape.vocab, 128, dtype=np.int32)
+        forced[check] = tok[0]
+        glp = g.decode_step_forced(ids, 1.0, forced)
+        dlp.append(float(glp[check]) - float(lp[0]))
+    from oracle.bf16_error_model import forward_bf16_model
+    zm = forward_bf16_model(o.model, toks, rows=[len(toks) - 1])[0]
+    fig = check_against_rounding_model(zg, zo, zm, dlp, "4B shape, context 2048")
+    print("4B shape at context 2048:", fig)
+    # masked log-prob pass over the whole trajectory against the log-probs of the 1027 decode steps
+    rec = g.recompute_logprobs([check], 1.0)
+    t2, m2, gen2, _ = g.traj_read(check)
+    assert np.array_equal(t2[:2048], toks) and np.count_nonzero(rec) == 1027 and np.all(rec[m2 == 1] == 0.0)
+    from tolerances import gaussian_max_factor
+    bound = np.sqrt(2.0) * gaussian_max_factor(1027) * fig["rms_model"]
+    print("recompute vs generation:", float(np.abs(rec - gen2)[m2 == 0].max()), "bound", bound)
+    assert np.abs(rec - gen2)[m2 == 0].max() < bound
+    g.close()
