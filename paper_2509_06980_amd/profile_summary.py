@@ -105,7 +105,10 @@ def mfma_table(counter_path, trace_path):
         for r in csv.DictReader(f):
             name = r["Kernel_Name"].split("(")[0]
             name = name[5:] if name.startswith("void ") else name
-            g = int(r.get("Grid_Size_X") or r.get("Grid_Size"))
+            if r.get("Grid_Size_X"):    # the counter file gives the total number of threads of a launch
+                g = int(r["Grid_Size_X"]) * int(r.get("Grid_Size_Y") or 1) * int(r.get("Grid_Size_Z") or 1)
+            else:
+                g = int(r["Grid_Size"])
             dur[name][g].append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
     peak = 2500.0
     print("# Matrix-core (MFMA) utilisation of the chunked-prefill kernels and the decode GEMMs "
@@ -134,7 +137,46 @@ def mfma_table(counter_path, trace_path):
         print(f"| {k[:64]} | {g} | {n} | {us:.1f} | {fl / 1e9:.1f} | {tf:.0f} | {tf / peak:.3f} |")
 
 
+def rollout_summary(trace_path, stats_path, bench_log):
+    """Kernel summary of a profiled bench.py run: the decode-attention launches by shape (kernel
+    trace), rocprofv3's own per-kernel statistics, and the figures bench.py printed in that run
+    (`bench_log`: its captured output; the last line starting with {"metric" is used)."""
+    import json
+    line = [l for l in open(bench_log).read().splitlines() if l.startswith('{"metric"')][-1]
+    b = json.loads(line)
+    r = b["roofline"]
+    print("# rocprofv3 kernel summary: attention_mfma_kernel and the rest of the cfg3 rollout "
+          "(Qwen3-4B shape, 128 trajectories)\n")
+    print("Commands (on the MI355X box, from the repository root):\n")
+    print("    cd /tmp && export TMPDIR=/tmp && cd <repository root> && rocprofv3 --kernel-trace --stats "
+          "--output-format csv -d out/prof_full -o cfg3 -- python3 bench.py --no-cpu-baseline > out/bench.log")
+    print("    python -m paper_2509_06980_amd.profile_summary --rollout out/prof_full/<host>/cfg3_kernel_trace.csv "
+          "out/prof_full/<host>/cfg3_kernel_stats.csv out/bench.log\n")
+    print("The run covers one warm-up rollout plus one timed rollout (2 x 2048 decode steps, 2 x 5 appends).\n")
+    print(f"bench.py line of the same run: value {b['value']} tokens/s, decode-only "
+          f"{b['decode_only_tokens_per_s']} tokens/s, decode-step HBM fraction {b['decode_step_hbm']['frac']} "
+          f"(distinct pages; {b['decode_step_hbm'].get('achieved_counting_shared_pages_per_trajectory')} GB/s when "
+          f"every trajectory is charged its whole context); roofline: {r['achieved']} GB/s over distinct pages "
+          f"({r['achieved_counting_shared_pages_per_trajectory']} GB/s counting shared prompt pages per trajectory), "
+          f"{r['avg_launch_us']} us per decode launch (HIP events around attention + merge, every 16th step), "
+          f"{r['bytes_per_launch']} bytes per launch; measured streaming-read ceiling of the box "
+          f"{b['measured_stream_read_GBs']} GB/s.\n")
+    print("attention_mfma_kernel<false> (the bf16-cache instance; decode launches: one workgroup per "
+          "trajectory x kv head) by launch shape, from the kernel trace:\n")
+    trace_summary(trace_path)
+    print("\nThe decode average agrees with the HIP-event figure of bench.py (the profiler adds a little "
+          "per-launch overhead to the event bracket). Chunked prefill runs in attention_prefill_mfma_kernel.\n")
+    print("| kernel | calls | total ms | avg us | % |\n|---|---|---|---|---|")
+    with open(stats_path, newline="") as f:
+        for x in csv.DictReader(f):
+            n = x["Name"][5:] if x["Name"].startswith("void ") else x["Name"]
+            print(f"| {n.split('(')[0]} | {x['Calls']} | {float(x['TotalDurationNs']) / 1e6:.1f} | "
+                  f"{float(x['AverageNs']) / 1e3:.2f} | {float(x['Percentage']):.2f} |")
+
+
 def main():
+    if sys.argv[1] == "--rollout":
+        return rollout_summary(sys.argv[2], sys.argv[3], sys.argv[4])
     if sys.argv[1] == "--trace":
         return trace_summary(sys.argv[2])
     if sys.argv[1] == "--mfma":
