@@ -221,3 +221,36 @@ def test_4b_shape_context_2048_decode_in_the_timed_launch_configuration():
     print("recompute vs generation:", float(np.abs(rec - gen2)[m2 == 0].max()), "bound", bound)
     assert np.abs(rec - gen2)[m2 == 0].max() < bound
     g.close()
+
+
+def test_decode_batch_of_260_rows_three_row_tiles():
+    # more active trajectories than two 128-row tiles hold (cfg5 runs 256 at once when memory
+    # allows): every GEMM of the decode step, the lm-head with its strip maxima and the sampler
+    # walk three row tiles, the last one ragged
+    shape = SHAPES["small-d128"]
+    blob = make_weight_blob(shape, seed=51, weight_std=0.03, gain_std=0.1)
+    n = 260
+    kw = dict(max_context=128, max_trajectories=n, kv_pool_pages=n * 6)
+    o, g = OracleEngine(blob, **kw), rl.RolloutEngine(blob, **kw)
+    rng = np.random.default_rng(9)
+    ids = rng.permutation(1000)[:n].astype(np.int32)
+    lens = rng.integers(3, 60, n)
+    toks = rng.integers(0, shape.vocab, int(lens.sum()))
+    o.append_observation(ids, toks, lens)
+    g.append_observation(ids, toks, lens)
+    for step, T in enumerate([1.0, 0.7, 0.0]):
+        tok, lps = o.decode_step(ids, T, 13)
+        glp = g.decode_step_forced(ids, T, tok)
+        assert np.abs(glp - lps).max() < TOL_BF16, (step, float(np.abs(glp - lps).max()))
+    # free-running step: the ids must be the oracle sampler's on the GPU's own logits
+    from oracle.sampler import sample_token, uniform_u32
+    probe = [0, 127, 128, 255, 256, 259]
+    z = {k: g.debug_logits(int(ids[k])) for k in probe}
+    out, lp = g.decode_step(ids, 1.0, 21)
+    for k in probe:
+        t, l = sample_token(z[k], 1.0, uniform_u32(21, int(ids[k]), int(lens[k]) + 3))
+        assert out[k] == t and abs(lp[k] - l) < TOL_FP32
+    o.decode_step_forced(ids, 1.0, out)
+    for k in probe:
+        compare_records(o, g, int(ids[k]))
+    assert o.n_free_pages() == g.n_free_pages()
