@@ -476,12 +476,13 @@ __device__ __forceinline__ u32x4 att_operand(const u32x4 (&R)[N], int i) {
     }                                                                         \
   }
 
+// row_stride: floats between the outputs of two MFMA columns of one part
 __device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
                                                  const float* __restrict__ pl,
                                                  const float* __restrict__ pacc, int nparts,
                                                  size_t part_stride_ml, size_t part_stride_acc,
-                                                 int n, int d0, float* m_out, float* l_out,
-                                                 float* o8) {
+                                                 int row_stride, int n, int d0, float* m_out,
+                                                 float* l_out, float* o8) {
   float mt = ATT_NEG;
   for (int w = 0; w < nparts; w++) mt = fmaxf(mt, pm[w * part_stride_ml + n]);
   float L = 0.f;
@@ -490,7 +491,7 @@ __device__ __forceinline__ void attn_merge_store(const float* __restrict__ pm,
   for (int w = 0; w < nparts; w++) {
     float f = exp2f(pm[w * part_stride_ml + n] - mt);
     L += f * pl[w * part_stride_ml + n];
-    const float* a = pacc + w * part_stride_acc + (size_t)n * 128 + d0;
+    const float* a = pacc + w * part_stride_acc + (size_t)n * row_stride + d0;
 #pragma unroll
     for (int e = 0; e < 8; e++) o8[e] += f * a[e];
   }
@@ -504,7 +505,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const AttnItem* __restrict__ items, const int32_t* __restrict__ rowlist,
     const int32_t* __restrict__ page_table, bf16_t* __restrict__ o, float* __restrict__ scratch,
     int nq, int nkv, int gshift, int pt_stride, float scale2) {
-  __shared__ float s_acc[4 * 16 * 128];
+  // a column's 128 outputs are padded to 132 floats: with a stride of 128 the 16 lanes that hold
+  // one token group's 16 columns would all store into the same 4 banks
+  constexpr int AST = 132;
+  __shared__ __align__(16) float s_acc[4 * 16 * AST];
   __shared__ float s_m[4 * 16];
   __shared__ float s_l[4 * 16];
   // blockIdx.x = item * nkv + kvh: consecutive workgroups go round-robin to the 8 XCDs, so with
@@ -564,15 +568,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   l += __shfl_xor(l, 32, 64);
   // wave partials -> LDS: acc[jb][i] is O^T[d = 16 jb + 4 g + i][column n]
 #pragma unroll
-  for (int jb = 0; jb < 8; jb++)
-#pragma unroll
-    for (int i = 0; i < 4; i++) s_acc[(wave * 16 + n) * 128 + jb * 16 + g * 4 + i] = acc[jb][i];
+  for (int jb = 0; jb < 8; jb++) *(f32x4*)&s_acc[(wave * 16 + n) * AST + jb * 16 + g * 4] = acc[jb];
   if (g == 0) { s_m[wave * 16 + n] = m; s_l[wave * 16 + n] = l; }
   __syncthreads();
   // 256 threads: column cn = tid / 16, dims d0 .. d0+7
   const int cn = tid >> 4, d0 = (tid & 15) * 8;
   float mt, L, o8[8];
-  attn_merge_store(s_m, s_l, s_acc, 4, 16, 16 * 128, cn, d0, &mt, &L, o8);
+  attn_merge_store(s_m, s_l, s_acc, 4, 16, 16 * AST, AST, cn, d0, &mt, &L, o8);
   const int cr = cn >> gshift, chq = cn & ((1 << gshift) - 1);
   if (it.part < 0) {
     if (cr < it.nrows) {

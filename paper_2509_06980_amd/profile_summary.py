@@ -174,7 +174,70 @@ def rollout_summary(trace_path, stats_path, bench_log):
                   f"{float(x['AverageNs']) / 1e3:.2f} | {float(x['Percentage']):.2f} |")
 
 
+def stall_table(path_a, path_b):
+    """Where the GEMM and attention kernels spend their cycles, per kernel and launch shape, from
+    two counter runs of the same command (a: wave / MFMA / wait counters of the SQ block,
+    b: GRBM_GUI_ACTIVE, texture-addresser and L1 stall counters).  Ratios:
+      MFMA busy   = SQ_VALU_MFMA_BUSY_CYCLES / (GRBM_GUI_ACTIVE / 8 XCDs x 1024 SIMDs)
+      waves wait  = SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES (share of resident wave time spent waiting)
+      ... on LDS  = SQ_WAIT_INST_LDS / SQ_WAVE_CYCLES
+      TA busy     = TA_TA_BUSY_sum / (GRBM_GUI_ACTIVE / 8 x 256 CUs)
+      L1 pending  = TCP_PENDING_STALL_CYCLES_sum / (GRBM_GUI_ACTIVE / 8 x 256 CUs)
+      clock       = GRBM_GUI_ACTIVE / 8 / kernel duration"""
+    def read_all(path):
+        out = defaultdict(lambda: defaultdict(lambda: defaultdict(list)))
+        dur = defaultdict(lambda: defaultdict(list))
+        with open(path, newline="") as f:
+            for r in csv.DictReader(f):
+                name = r["Kernel_Name"].split("(")[0]
+                name = name[5:] if name.startswith("void ") else name
+                g = int(r["Grid_Size"])
+                out[name][g][r["Counter_Name"]].append(float(r["Counter_Value"]))
+                if r["Counter_Name"] == "GRBM_GUI_ACTIVE":
+                    dur[name][g].append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+        return out, dur
+    a, _ = read_all(path_a)
+    b, dur = read_all(path_b)
+    mean = lambda v: sum(v) / len(v) if v else float("nan")
+    print("# Stall profile of the GEMM and attention kernels (Qwen3-4B shape, 128 trajectories, half lengths)\n")
+    print("Commands (MI355X box, repository root; two counter sets, one run each):\n")
+    print("    rocprofv3 --pmc SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAIT_INST_LDS SQ_WAIT_INST_ANY "
+          "SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE --kernel-include-regex 'gemm_mfma|attention' --output-format csv "
+          "-d out/pmc_sq_a -o a -- python3 bench.py --warmup 0 --no-cpu-baseline --scale 0.5")
+    print("    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_LDS_DATA_FIFO_FULL SQ_LDS_CMD_FIFO_FULL TA_TA_BUSY_sum "
+          "TA_ADDR_STALLED_BY_TC_CYCLES_sum TCP_PENDING_STALL_CYCLES_sum TCP_TCP_TA_DATA_STALL_CYCLES_sum "
+          "--kernel-include-regex 'gemm_mfma|attention' --output-format csv -d out/pmc_sq_b -o b -- python3 bench.py "
+          "--warmup 0 --no-cpu-baseline --scale 0.5")
+    print("    python -m paper_2509_06980_amd.profile_summary --stalls <a_counter_collection.csv> <b_counter_collection.csv>\n")
+    print("GRBM_GUI_ACTIVE is summed over the 8 XCDs; durations are those of the counter run (kernels run one at a "
+          "time there).  MFMA busy counts issue cycles of the matrix pipes against 1024 SIMDs.  The clock column is "
+          "GRBM_GUI_ACTIVE over the kernel's duration: meaningful for the long kernels only (for kernels of a few "
+          "tens of microseconds the counter window includes the launch, and the figure reads high).\n")
+    print("| kernel | grid (threads) | dispatches | avg us | clock GHz | MFMA busy | waves wait | ... on LDS | LDS bank conflicts | TA busy | L1 pending-miss stall |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    rows = []
+    for k, grids in b.items():
+        for g, cb in grids.items():
+            ca = a.get(k, {}).get(g)
+            if not ca or len(cb.get("GRBM_GUI_ACTIVE", [])) < 20:
+                continue
+            gui = mean(cb["GRBM_GUI_ACTIVE"]) / 8.0
+            us = mean(dur[k][g]) / 1e3
+            wave = mean(ca["SQ_WAVE_CYCLES"])
+            rows.append((k, g, len(cb["GRBM_GUI_ACTIVE"]), us, gui / (us * 1e3),
+                         mean(ca["SQ_VALU_MFMA_BUSY_CYCLES"]) / (gui * 1024.0),
+                         mean(ca["SQ_WAIT_INST_ANY"]) / wave, mean(ca["SQ_WAIT_INST_LDS"]) / wave,
+                         mean(ca["SQ_LDS_BANK_CONFLICT"]),
+                         mean(cb["TA_TA_BUSY_sum"]) / (gui * 256.0),
+                         mean(cb["TCP_PENDING_STALL_CYCLES_sum"]) / (gui * 256.0)))
+    for r in sorted(rows, key=lambda r: -r[2] * r[3]):
+        print(f"| {r[0][:56]} | {r[1]} | {r[2]} | {r[3]:.1f} | {r[4]:.2f} | {r[5]:.2f} | {r[6]:.2f} | {r[7]:.2f} | "
+              f"{r[8]:.0f} | {r[9]:.2f} | {r[10]:.2f} |")
+
+
 def main():
+    if sys.argv[1] == "--stalls":
+        return stall_table(sys.argv[2], sys.argv[3])
     if sys.argv[1] == "--rollout":
         return rollout_summary(sys.argv[2], sys.argv[3], sys.argv[4])
     if sys.argv[1] == "--trace":
