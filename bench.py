@@ -51,8 +51,11 @@ def recorded_traffic(config):
     return None
 
 
-def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
+def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0, single_step_calls=False):
     """Replay the workload once (free-running sampling); returns generated token count.
+    Consecutive decode events of the same trajectories (a generation turn of known length) go to the
+    engine as ONE rl_decode_steps call unless single_step_calls is set: same tokens, log-probs and
+    state, but the host does not wait for every token.
     fuse_appends: an append event directly followed by a decode event is issued as one call
     (rl_decode_step_with_appends); its time is booked under the decode step."""
     kvtok = shape.kv_bytes_per_token() * kv_scale      # kv_scale 0.5: 8-bit cache variant
@@ -61,7 +64,9 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
     n_gen = 0
     pending_append = None
     events = w.events
-    for k, ev in enumerate(events):
+    k = 0
+    while k < len(events):
+        ev = events[k]
         kind = ev[0]
         if fuse_appends and kind == "append" and k + 1 < len(events) and events[k + 1][0] == "decode":
             pending_append = ev
@@ -69,6 +74,7 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
             for i, c in zip(ev[1], ev[3]):
                 ctx[int(i)] = ctx.get(int(i), 0) + int(c)
             stats["fused_appends"] = stats.get("fused_appends", 0) + 1
+            k += 1
             continue
         if kind != "decode" and stats.get("turns"):
             stats["turns"][-1]["closed"] = True
@@ -90,54 +96,67 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0):
             for d in ev[2]:
                 ctx[int(d)] = ctx[int(ev[1])]
         elif kind == "decode":
+            # K = number of consecutive decode events of the same trajectories, temperature and seed
+            K = 1
+            if pending_append is None and not single_step_calls:
+                while (k + K < len(events) and events[k + K][0] == "decode" and events[k + K][2] == ev[2]
+                       and events[k + K][3] == ev[3] and np.array_equal(events[k + K][1], ev[1])):
+                    K += 1
             t0 = time.perf_counter()
             if pending_append is not None:
                 engine.decode_step_with_appends(pending_append[1], pending_append[2], pending_append[3],
                                                 ev[1], ev[2], ev[3])
                 pending_append = None
+            elif K > 1:
+                engine.decode_steps(ev[1], K, ev[2], ev[3])
             else:
                 engine.decode_step(ev[1], ev[2], ev[3])
             dt = time.perf_counter() - t0
             stats["decode_s"] += dt
-            tot = 0
+            stats["decode_calls"] = stats.get("decode_calls", 0) + 1
+            n_act = len(ev[1])
+            tot = sum(ctx[int(i)] for i in ev[1])          # contexts at the first of the K steps
             for i in ev[1]:
-                tot += ctx[int(i)]
-                ctx[int(i)] += 1
-            # algorithmic bytes of this decode step: weights once, every cached key/value of a
-            # DISTINCT page once (the engine counts a page that a forked group shares once per
-            # step), one new key/value row per trajectory.  The count that charges every
-            # trajectory its whole context is kept beside it under its own name.
-            nbytes_traj = wbytes + (tot + len(ev[1])) * kvtok
+                ctx[int(i)] += K
+            # algorithmic bytes of these decode steps: weights once per step, every cached key/value
+            # of a DISTINCT page once per step (the engine counts a page that a forked group shares
+            # once per step), one new key/value row per trajectory and step.  The count that charges
+            # every trajectory its whole context is kept beside it under its own name.
+            tot_all = K * tot + n_act * K * (K - 1) // 2     # sum over the K steps of the contexts
+            nbytes_traj = K * wbytes + (tot_all + K * n_act) * kvtok
             kv_b, kv_u, acc_n = engine.timing_read_decode_bytes(reset=True)
-            if acc_n == 1:
-                nbytes = wbytes + kv_u * shape.n_layers + len(ev[1]) * kvtok
+            if acc_n == K:
+                nbytes = K * wbytes + kv_u * shape.n_layers + K * n_act * kvtok
             else:       # accounting off (warm-up) or a step that also carried appended rows
                 nbytes = nbytes_traj
-                stats["decode_steps_without_page_accounting"] = stats.get("decode_steps_without_page_accounting", 0) + 1
+                stats["decode_steps_without_page_accounting"] = stats.get("decode_steps_without_page_accounting", 0) + K
             stats["decode_bytes"] += nbytes
             stats["decode_bytes_per_trajectory"] = stats.get("decode_bytes_per_trajectory", 0.0) + nbytes_traj
-            stats["decode_steps"] += 1
-            if stats["decode_steps"] % 512 == 0:     # progress of the work itself
-                print(f"[bench] {stats['decode_steps']} decode steps, mean context {tot / len(ev[1]):.0f}, "
+            before = stats["decode_steps"]
+            stats["decode_steps"] += K
+            if before // 512 != stats["decode_steps"] // 512:     # progress of the work itself
+                print(f"[bench] {stats['decode_steps']} decode steps, mean context {(tot + n_act * (K - 1)) / n_act:.0f}, "
                       f"{stats['decode_s']:.1f}s in decode, {stats['append_s']:.1f}s in appends",
                       file=sys.stderr, flush=True)
-            n_gen += len(ev[1])
+            n_gen += n_act * K
             # the same figures per run of consecutive decode steps (one generation turn)
             turns = stats.setdefault("turns", [])
             if not turns or turns[-1]["closed"]:
                 turns.append(dict(closed=False, steps=0, s=0.0, bytes=0.0, bytes_traj=0.0, tokens=0,
-                                  ctx_first=tot / len(ev[1]), ctx_last=0.0))
+                                  ctx_first=tot / n_act, ctx_last=0.0))
             tr = turns[-1]
-            tr["steps"] += 1
+            tr["steps"] += K
             tr["s"] += dt
             tr["bytes"] += nbytes
             tr["bytes_traj"] += nbytes_traj
-            tr["tokens"] += len(ev[1])
-            tr["ctx_last"] = tot / len(ev[1])
+            tr["tokens"] += n_act * K
+            tr["ctx_last"] = (tot + n_act * (K - 1)) / n_act
+            k += K - 1
         elif kind == "release":
             engine.release(ev[1])
             for i in ev[1]:
                 ctx.pop(int(i), None)
+        k += 1
     if ctx:   # workload without a final release (cfg5): recompute all log-probs, then release
         ids = np.array(sorted(ctx), np.int32)
         gen = {int(i): engine.traj_read(int(i)) for i in ids[:4]}
@@ -295,6 +314,9 @@ def main():
                     help="decode attention reads a forked group's shared pages once per block of members")
     ap.add_argument("--fp8-kv-cache", action="store_true",
                     help="variant, never the headline: keys / values cached as E4M3 codes (half the cache bytes)")
+    ap.add_argument("--single-step-calls", action="store_true",
+                    help="one rl_decode_step call per token (the host waits for every token) instead of one "
+                         "rl_decode_steps call per run of decode steps of the same trajectories")
     ap.add_argument("--fuse-appends", action="store_true",
                     help="issue an append that is directly followed by a decode step as one call")
     ap.add_argument("--tool-loop", action="store_true",
@@ -334,7 +356,7 @@ def main():
     for i in range(args.warmup):
         t0 = time.perf_counter()
         run_rollout(eng, w, shape, dict(append_s=0.0, decode_s=0.0, decode_bytes=0.0, decode_steps=0),
-                    args.fuse_appends, kv_scale)
+                    args.fuse_appends, kv_scale, args.single_step_calls)
         print(f"[bench] warmup {i}: {time.perf_counter() - t0:.2f}s", file=sys.stderr, flush=True)
 
     eng.timing_enable(args.timing_every)
@@ -344,7 +366,7 @@ def main():
     t0 = time.perf_counter()
     n_gen = 0
     for i in range(args.steps):
-        n_gen += run_rollout(eng, w, shape, stats, args.fuse_appends, kv_scale)
+        n_gen += run_rollout(eng, w, shape, stats, args.fuse_appends, kv_scale, args.single_step_calls)
         print(f"[bench] step {i}: {time.perf_counter() - t0:.2f}s elapsed", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -380,6 +402,9 @@ def main():
                    "decode_steps_per_step": w.n_decode_steps, "max_context": w.max_context,
                    "scale": args.scale, "shared_prefix_attention": bool(args.shared_prefix_attention),
                    "fuse_appends": bool(args.fuse_appends),
+                   "decode_calls": "rl_decode_step per token" if args.single_step_calls else
+                   "rl_decode_steps per run of decode steps of the same trajectories",
+                   "decode_calls_per_step": stats.get("decode_calls"),
                    "kv_cache": "fp8_e4m3 (variant: not the bf16 contract of the headline)" if args.fp8_kv_cache else "bf16"},
         "measured_stream_read_GBs": round(stream_gbs, 1),
         "decode_only_tokens_per_s": round(n_gen / stats["decode_s"], 1) if stats["decode_s"] else None,

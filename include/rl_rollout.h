@@ -119,6 +119,22 @@ int rl_decode_step(rl_model* m, const int32_t* active_traj_ids, int32_t n, float
                    uint64_t rng_seed, int32_t* token_ids_out, float* logprobs_out);
 
 /*
+ * Generate step repeated (Section 2.3.2: the model generates a response token by token until the
+ * Parse step looks at it): exactly n_steps calls of rl_decode_step(active_traj_ids, n, temperature,
+ * rng_seed, ...) in a row, in one call.  token_ids_out and logprobs_out hold n_steps x n entries,
+ * step-major (entry s * n + i belongs to step s, trajectory active_traj_ids[i]).  Results, state and
+ * page indices are identical, bit for bit, to the single steps; what differs is the timing: a
+ * sampled token feeds the next step on the device, and the host stages the following steps while the
+ * GPU works instead of waiting for every step's ids, so the GPU does not idle between steps.  The
+ * caller decides how many tokens to generate before it looks at them (a turn of known length, or a
+ * window after which it checks for a tool call).  All or nothing over the whole call: context
+ * overflow and page needs are checked for all n_steps tokens before anything changes.
+ * n_steps = 0 is allowed.  Errors: as rl_decode_step.
+ */
+int rl_decode_steps(rl_model* m, const int32_t* active_traj_ids, int32_t n, int32_t n_steps,
+                    float temperature, uint64_t rng_seed, int32_t* token_ids_out, float* logprobs_out);
+
+/*
  * Update + Generate in one pass (continuous batching, Section 2.3.2: tool calls return at different
  * times, the batch must not wait): exactly rl_append_observation(app_*) followed by
  * rl_decode_step(active_traj_ids, ...), but the appended tokens' keys / values are computed in the

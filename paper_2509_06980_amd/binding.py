@@ -8,7 +8,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librl_rollo
 
 EXPORTED_SYMBOLS = [
     "rl_model_load", "rl_model_free", "rl_model_get_config", "rl_last_error",
-    "rl_append_observation", "rl_decode_step", "rl_release", "rl_fork", "rl_traj_info",
+    "rl_append_observation", "rl_decode_step", "rl_decode_steps", "rl_release", "rl_fork", "rl_traj_info",
     "rl_traj_read", "rl_free_pages", "rl_recompute_logprobs", "rl_debug_logits",
     "rl_decode_step_forced", "rl_sample_from_logits", "rl_sample_device_logits", "rl_uniform_u32", "rl_timing_enable",
     "rl_timing_read", "rl_timing_read_steps", "rl_timing_read_decode_bytes", "rl_measure_stream_read",
@@ -62,6 +62,7 @@ def load_library():
     lib.rl_model_get_config.argtypes = [C.c_void_p, C.POINTER(_ModelConfig)]
     lib.rl_append_observation.argtypes = [C.c_void_p, _I32P, C.c_int32, _I32P, _I32P]
     lib.rl_decode_step.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_float, C.c_uint64, _I32P, _F32P]
+    lib.rl_decode_steps.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_int32, C.c_float, C.c_uint64, _I32P, _F32P]
     lib.rl_decode_step_forced.argtypes = [C.c_void_p, _I32P, C.c_int32, C.c_float, _I32P, _F32P]
     lib.rl_decode_step_with_appends.argtypes = [C.c_void_p, _I32P, C.c_int32, _I32P, _I32P, _I32P, C.c_int32,
                                                 C.c_float, C.c_uint64, _I32P, _F32P]
@@ -182,6 +183,17 @@ class RolloutEngine:
         _check(self._lib.rl_decode_step(self._h, pi, ids.size, float(temperature),
                                         C.c_uint64(int(rng_seed) & (2**64 - 1)),
                                         out.ctypes.data_as(_I32P), lps.ctypes.data_as(_F32P)))
+        return out, lps
+
+    def decode_steps(self, traj_ids, n_steps, temperature, rng_seed):
+        """n_steps decode steps of the same trajectories in one call -> (ids, logprobs), each of
+        shape [n_steps, n]."""
+        ids, pi = _i32(traj_ids)
+        out = np.empty((max(int(n_steps), 0), ids.size), np.int32)
+        lps = np.empty((max(int(n_steps), 0), ids.size), np.float32)
+        _check(self._lib.rl_decode_steps(self._h, pi, ids.size, int(n_steps), float(temperature),
+                                         C.c_uint64(int(rng_seed) & (2**64 - 1)),
+                                         out.ctypes.data_as(_I32P), lps.ctypes.data_as(_F32P)))
         return out, lps
 
     def decode_step_forced(self, traj_ids, temperature, forced_token_ids):

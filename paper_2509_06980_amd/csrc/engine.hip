@@ -83,6 +83,11 @@ struct rl_model {
   size_t meta_ints = 0;
   SamplerScratch ss{};
   int32_t *d_ids = nullptr, *h_ids = nullptr;
+  // several decode steps in one call: per-step ids / log-probs on the device and pinned, and one
+  // event per staging region (the host runs that many steps ahead of the GPU)
+  int32_t *d_ids_hist = nullptr, *h_ids_hist = nullptr;
+  float *d_lp_hist = nullptr, *h_lp_hist = nullptr;
+  std::vector<hipEvent_t> ev_region;
   float *d_lp = nullptr, *h_lp = nullptr;
   float* d_stripmax = nullptr;   // [Rl, V / 32] maxima of 32-logit strips from the lm-head epilogue
   float *d_zt = nullptr, *d_lp_rows = nullptr, *h_lp_rows = nullptr;   // masked log-prob pass: Mcap rows
@@ -319,7 +324,9 @@ struct DevMeta {
 
 int check_pass(rl_model* m, const Staging& st, int slots_used);
 
-int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
+// at: offset (in ints) of the region of the staging buffers this pass uses (0 unless several
+// passes are staged ahead of the GPU)
+int upload_meta(rl_model* m, const Staging& st, DevMeta* dm, size_t at = 0) {
   size_t M = st.tok.size();
   {
     int slots = 0;
@@ -329,8 +336,9 @@ int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   }
   static_assert(sizeof(AttnItem) == 32 && sizeof(AttnMerge) == 32, "metadata records are 8 ints");
   size_t need = 6 * M + 8 * st.items.size() + 8 * st.merges.size() + st.rowlist.size();
-  if (need > m->meta_ints) return fail(RL_E_ARG, "internal: metadata staging too small");
-  int32_t* h = m->h_meta;
+  if (at + need > m->meta_ints) return fail(RL_E_ARG, "internal: metadata staging too small");
+  int32_t* h = m->h_meta + at;
+  int32_t* d = m->d_meta + at;
   auto put = [&](const std::vector<int32_t>& v, size_t at) {
     if (!v.empty()) memcpy(h + at, v.data(), v.size() * 4);
   };
@@ -340,12 +348,12 @@ int upload_meta(rl_model* m, const Staging& st, DevMeta* dm) {
   if (!st.merges.empty())
     memcpy(h + 6 * M + 8 * st.items.size(), st.merges.data(), st.merges.size() * sizeof(AttnMerge));
   put(st.rowlist, 6 * M + 8 * st.items.size() + 8 * st.merges.size());
-  HIPCHECK(hipMemcpyAsync(m->d_meta, h, need * 4, hipMemcpyHostToDevice, m->stream));
-  dm->tok = m->d_meta; dm->pos = m->d_meta + M; dm->slot = m->d_meta + 2 * M;
-  dm->traj = m->d_meta + 3 * M; dm->newpos = m->d_meta + 4 * M; dm->forced = m->d_meta + 5 * M;
-  dm->items = (AttnItem*)(m->d_meta + 6 * M);
-  dm->merges = (AttnMerge*)(m->d_meta + 6 * M + 8 * st.items.size());
-  dm->rowlist = m->d_meta + 6 * M + 8 * st.items.size() + 8 * st.merges.size();
+  HIPCHECK(hipMemcpyAsync(d, h, need * 4, hipMemcpyHostToDevice, m->stream));
+  dm->tok = d; dm->pos = d + M; dm->slot = d + 2 * M;
+  dm->traj = d + 3 * M; dm->newpos = d + 4 * M; dm->forced = d + 5 * M;
+  dm->items = (AttnItem*)(d + 6 * M);
+  dm->merges = (AttnMerge*)(d + 6 * M + 8 * st.items.size());
+  dm->rowlist = d + 6 * M + 8 * st.items.size() + 8 * st.merges.size();
   if (!st.mask.empty())
     HIPCHECK(hipMemcpyAsync(m->d_mask, st.mask.data(), st.mask.size(), hipMemcpyHostToDevice, m->stream));
   return RL_OK;
@@ -708,6 +716,160 @@ int decode_impl(rl_model* m, const int32_t* ids, int32_t n, float temperature, u
   return RL_OK;
 }
 
+// Several decode steps of one list of trajectories in one call.  The result is that of n_steps
+// single steps; the difference is in the timing: the token a step samples stays on the device and
+// feeds the next step's embedding lookup there, the metadata of the steps is staged in regions of
+// the staging buffers, and the host runs up to one region per step ahead of the GPU instead of
+// waiting for every step's ids.  Pages for the whole call are reserved up front, in the order the
+// single steps would have taken them.
+const int kMaxStepsPerChunk = 1024;
+
+int decode_multi(rl_model* m, const int32_t* ids, int32_t n, int32_t n_steps, float temperature,
+                 uint64_t seed, int32_t* ids_out, float* lp_out) {
+  int rc = check_ids(ids, n);
+  if (rc) return rc;
+  if (n_steps < 0) return fail(RL_E_ARG, "negative step count");
+  if (!(temperature >= 0.0f)) return fail(RL_E_ARG, "negative temperature");
+  if (n > 0 && n_steps > 0 && (!ids_out || !lp_out)) return fail(RL_E_ARG, "null output");
+  if (n > m->rt.max_trajectories) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+  std::vector<Traj*> ts(n);
+  for (int i = 0; i < n; i++) {
+    auto it = m->traj.find(ids[i]);
+    if (it == m->traj.end()) return fail(RL_E_BAD_TRAJ, "unknown trajectory id");
+    ts[i] = &it->second;
+  }
+  for (Traj* t : ts)
+    if (t->tokens.empty()) return fail(RL_E_EMPTY, "trajectory has no context");
+  int64_t need = 0;
+  for (Traj* t : ts) {
+    const int64_t after = (int64_t)t->tokens.size() + n_steps;
+    if (after > m->rt.max_context) return fail(RL_E_CTX_OVERFLOW, "context overflow");
+    need += (after + RL_PAGE - 1) / RL_PAGE - (int64_t)t->pages.size();
+  }
+  if (need > m->n_free) return fail(RL_E_NOPAGES, "page pool exhausted");
+  if (n == 0 || n_steps == 0) return RL_OK;
+  {
+    std::vector<int32_t> upd;
+    std::vector<size_t> len0(n);
+    for (int i = 0; i < n; i++) len0[i] = ts[i]->tokens.size();
+    for (int sidx = 0; sidx < n_steps; sidx++)
+      for (int i = 0; i < n; i++)
+        if ((len0[i] + sidx) % RL_PAGE == 0) {
+          Traj* t = ts[i];
+          int p = take_page(m);
+          upd.insert(upd.end(), {t->slot, (int32_t)t->pages.size(), p});
+          t->pages.push_back(p);
+        }
+    if (!upd.empty()) { rc = push_page_updates(m, upd); if (rc) return rc; }
+  }
+  // one staging region per step; the host may run as many steps ahead as there are regions
+  const size_t region_ints = 7 * (size_t)n + 8 * (size_t)(2 * n + m->attn_slots + 8);
+  const int n_regions = (int)std::min<size_t>(m->meta_ints / region_ints, 64);
+  if (n_regions < 1) return fail(RL_E_ARG, "internal: metadata staging too small");
+  while ((int)m->ev_region.size() < n_regions) {
+    hipEvent_t e = nullptr;
+    HIPCHECK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    m->ev_region.push_back(e);
+  }
+  const bool greedy = temperature == 0.0f;
+  const float c = (float)(1.4426950408889634 / (greedy ? 1.0 : (double)temperature));
+  float* stripmax = (m->mfma && !greedy) ? m->d_stripmax : nullptr;
+  const double tokb = 2.0 * m->md.nkv * m->md.d * m->kv_el;
+  Staging st;
+  for (int s0 = 0; s0 < n_steps; s0 += kMaxStepsPerChunk) {
+    const int C = std::min(kMaxStepsPerChunk, n_steps - s0);
+    std::vector<int> len0(n);
+    for (int i = 0; i < n; i++) len0[i] = (int)ts[i]->tokens.size();
+    for (int sc = 0; sc < C; sc++) {
+      const int region = sc % n_regions;
+      if (sc >= n_regions) HIPCHECK(hipEventSynchronize(m->ev_region[region]));
+      st.clear();
+      double kvb = 0.0;
+      for (int i = 0; i < n; i++) {
+        const int nt = len0[i] + sc;              // context length at this step
+        st.tok.push_back(sc == 0 ? ts[i]->tokens[nt - 1] : 0);   // later steps: the id sampled on the device
+        st.pos.push_back(nt - 1);
+        st.slot.push_back(ts[i]->slot);
+        st.traj.push_back(ids[i]);
+        st.newpos.push_back(nt);
+        kvb += (double)nt * tokb;
+      }
+      add_decode_items(m, st, ts);
+      {
+        const size_t need_ints = 6 * (size_t)n + 8 * st.items.size() + 8 * st.merges.size() + st.rowlist.size();
+        if (need_ints > region_ints) return fail(RL_E_ARG, "internal: staging region too small");
+      }
+      DevMeta dm;
+      rc = upload_meta(m, st, &dm, (size_t)region * region_ints);
+      if (rc) return rc;
+      const bool timed = m->timing_every > 0 && (m->decode_steps % m->timing_every) == 0;
+      m->decode_steps++;
+      const int32_t* tok = sc == 0 ? dm.tok : m->d_ids_hist + (size_t)(sc - 1) * n;
+      RowMeta r{tok, dm.pos, dm.slot, dm.items, (int)st.items.size(), dm.merges, (int)st.merges.size(),
+                dm.rowlist, nullptr, 0, false, kvb, timed};
+      if (timed) (void)hipEventRecord(m->ev_step[0], m->stream);
+      forward_rows(m, n, r);
+      lm_head_rows(m, n, 0, n, false, n, stripmax);
+      launch_sampler(m->stream, m->logits, (size_t)m->md.V, n, m->md.V, c, greedy ? 1 : 0, nullptr, seed,
+                     dm.traj, dm.newpos, nullptr, nullptr, m->ss, m->d_ids_hist + (size_t)sc * n,
+                     m->d_lp_hist + (size_t)sc * n, stripmax, m->md.V / 32);
+      HIPCHECK(hipGetLastError());
+      if (timed) (void)hipEventRecord(m->ev_step[1], m->stream);
+      HIPCHECK(hipEventRecord(m->ev_region[region], m->stream));
+      double kvu = 0.0;
+      if (m->timing_every > 0) {    // byte accounting, while the GPU works (as in the single step)
+        if (m->page_stamp.size() != m->refcount.size()) m->page_stamp.assign(m->refcount.size(), 0);
+        m->stamp++;
+        for (int i = 0; i < n; i++) {
+          const int nt = len0[i] + sc;
+          for (int pg = 0; pg * RL_PAGE < nt; pg++) {
+            const int page = ts[i]->pages[pg];
+            if (m->page_stamp[page] == m->stamp) continue;
+            m->page_stamp[page] = m->stamp;
+            kvu += tokb * std::min(RL_PAGE, nt - pg * RL_PAGE);
+          }
+        }
+        m->acct_kv_bytes += kvb;
+        m->acct_kv_unique_bytes += kvu;
+        m->acct_steps++;
+      }
+      if (timed) {    // a timed step is waited for: its events are read before they are reused
+        HIPCHECK(hipStreamSynchronize(m->stream));
+        float sms = 0.f;
+        if (hipEventElapsedTime(&sms, m->ev_step[0], m->ev_step[1]) == hipSuccess) {
+          m->step_gpu_ms += sms;
+          m->steps_timed++;
+        }
+        for (int l = 0; l < m->md.L; l++) {
+          float ms = 0.f;
+          if (hipEventElapsedTime(&ms, m->ev[2 * l], m->ev[2 * l + 1]) == hipSuccess) {
+            m->attn_ms += ms;
+            m->attn_launches++;
+            m->attn_bytes += kvb;
+            m->attn_unique_bytes += kvu;
+          }
+        }
+      }
+    }
+    HIPCHECK(hipMemcpyAsync(m->h_ids_hist, m->d_ids_hist, (size_t)C * n * 4, hipMemcpyDeviceToHost, m->stream));
+    HIPCHECK(hipMemcpyAsync(m->h_lp_hist, m->d_lp_hist, (size_t)C * n * 4, hipMemcpyDeviceToHost, m->stream));
+    HIPCHECK(hipStreamSynchronize(m->stream));
+    for (int sc = 0; sc < C; sc++)
+      for (int i = 0; i < n; i++) {
+        Traj* t = ts[i];
+        const int32_t id = m->h_ids_hist[(size_t)sc * n + i];
+        const float lp = m->h_lp_hist[(size_t)sc * n + i];
+        t->tokens.push_back(id);
+        t->mask.push_back(0);
+        t->logp.push_back(lp);
+        ids_out[(size_t)(s0 + sc) * n + i] = id;
+        lp_out[(size_t)(s0 + sc) * n + i] = lp;
+      }
+    for (Traj* t : ts) t->n_cached = (int)t->tokens.size() - 1;
+  }
+  return RL_OK;
+}
+
 int decode_common(rl_model* m, const int32_t* ids, int32_t n, float temperature, uint64_t seed,
                   const int32_t* forced, int32_t* ids_out, float* lp_out,
                   const std::vector<std::pair<Traj*, int>>* extra = nullptr) {
@@ -896,6 +1058,10 @@ extern "C" int rl_model_load(const rl_runtime_config* rt, const void* weights, s
   TRY(m->dalloc((void**)&m->ss.segw, (size_t)m->Rl * nseg * 8));
   TRY(m->dalloc((void**)&m->ss.sege, (size_t)m->Rl * nseg * 4));
   if (m->mfma) TRY(m->dalloc((void**)&m->d_stripmax, (size_t)m->Rl * (V / 32) * 4));
+  TRY(m->dalloc((void**)&m->d_ids_hist, (size_t)kMaxStepsPerChunk * m->Rl * 4));
+  TRY(m->dalloc((void**)&m->d_lp_hist, (size_t)kMaxStepsPerChunk * m->Rl * 4));
+  HIPTRY(hipHostMalloc((void**)&m->h_ids_hist, (size_t)kMaxStepsPerChunk * m->Rl * 4));
+  HIPTRY(hipHostMalloc((void**)&m->h_lp_hist, (size_t)kMaxStepsPerChunk * m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_ids, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_lp, (size_t)m->Rl * 4));
   TRY(m->dalloc((void**)&m->d_mask, Mc));
@@ -932,6 +1098,9 @@ extern "C" void rl_model_free(rl_model* m) {
   for (void* p : m->allocs) (void)hipFree(p);
   if (m->h_meta) (void)hipHostFree(m->h_meta);
   if (m->h_ids) (void)hipHostFree(m->h_ids);
+  if (m->h_ids_hist) (void)hipHostFree(m->h_ids_hist);
+  if (m->h_lp_hist) (void)hipHostFree(m->h_lp_hist);
+  for (auto e : m->ev_region) if (e) (void)hipEventDestroy(e);
   if (m->h_lp) (void)hipHostFree(m->h_lp);
   if (m->h_lp_rows) (void)hipHostFree(m->h_lp_rows);
   if (m->h_gaux) (void)hipHostFree(m->h_gaux);
@@ -1043,6 +1212,13 @@ extern "C" int rl_decode_step(rl_model* m, const int32_t* ids, int32_t n, float 
   if (!m) return fail(RL_E_ARG, "null model");
   if (n > 0 && !token_ids_out) return fail(RL_E_ARG, "null output");
   return decode_common(m, ids, n, temperature, rng_seed, nullptr, token_ids_out, logprobs_out);
+}
+
+extern "C" int rl_decode_steps(rl_model* m, const int32_t* ids, int32_t n, int32_t n_steps,
+                               float temperature, uint64_t rng_seed, int32_t* token_ids_out,
+                               float* logprobs_out) {
+  if (!m) return fail(RL_E_ARG, "null model");
+  return decode_multi(m, ids, n, n_steps, temperature, rng_seed, token_ids_out, logprobs_out);
 }
 
 extern "C" int rl_decode_step_forced(rl_model* m, const int32_t* ids, int32_t n, float temperature,

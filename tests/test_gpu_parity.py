@@ -84,6 +84,72 @@ def test_mfma_decode_step_sampler_with_strip_maxima_is_bit_exact(n_rows):
             assert out[k] == tok and abs(lps[k] - lp) < TOL_FP32, (n_rows, step, k)
 
 
+@pytest.mark.parametrize("name,flags,steps", [("tiny", 0, 40), ("tiny-bf16", 0, 21), ("small-d128", 0, 70),
+                                              ("small-d128", 2, 37), ("small-d128", 4, 37), ("small-g8", 0, 19),
+                                              ("tiny", 0, 1030)])
+def test_decode_steps_equals_the_single_steps_bit_for_bit(name, flags, steps):
+    # rl_decode_steps is n_steps single steps in one call (the sampled token feeds the next step on
+    # the device, the host stages ahead): ids, log-probs, records, page indices and the free list
+    # must be identical, also across page boundaries, more steps than staging regions (64), more
+    # than one chunk of steps (1024), a forked group, and a following append + second call
+    shape = SHAPES[name]
+    blob = make_weight_blob(shape, seed=61, weight_std=0.05, gain_std=0.1)
+    kw = dict(max_context=1400 if steps > 1000 else 256, max_trajectories=8,
+              kv_pool_pages=8 * 90 if steps > 1000 else 8 * 18, flags=flags)
+    a, b = rl.RolloutEngine(blob, **kw), rl.RolloutEngine(blob, **kw)
+    rng = np.random.default_rng(steps)
+    lens = [33, 5, 16, 47]
+    toks = rng.integers(0, shape.vocab, sum(lens))
+    ids = [3, 0, 9, 4, 12, 13]
+    for e in (a, b):
+        e.append_observation(ids[:4], toks, lens)
+        e.fork(3, [12, 13])
+    single = [a.decode_step(ids, 1.0, 5) for _ in range(steps)]
+    multi_ids, multi_lps = b.decode_steps(ids, steps, 1.0, 5)
+    assert multi_ids.shape == (steps, 6)
+    assert np.array_equal(multi_ids, np.stack([x[0] for x in single]))
+    assert np.array_equal(multi_lps, np.stack([x[1] for x in single]))
+    obs = rng.integers(0, shape.vocab, 23)
+    for e in (a, b):
+        e.append_observation([9, 13], obs, [20, 3])
+    s2 = [a.decode_step([13, 9, 0], 0.7 if k % 2 else 0.0, 8) for k in range(4)]
+    m0 = b.decode_steps([13, 9, 0], 1, 0.0, 8)
+    m1 = b.decode_steps([13, 9, 0], 1, 0.7, 8)
+    m2 = b.decode_steps([13, 9, 0], 1, 0.0, 8)
+    m3 = b.decode_steps([13, 9, 0], 1, 0.7, 8)
+    for k, mm in enumerate((m0, m1, m2, m3)):
+        assert np.array_equal(mm[0][0], s2[k][0]) and np.array_equal(mm[1][0], s2[k][1])
+    for t in ids:
+        ra, rb = a.traj_read(t), b.traj_read(t)
+        assert all(np.array_equal(x, y) for x, y in zip(ra, rb)), t
+    assert a.n_free_pages() == b.n_free_pages()
+    assert np.array_equal(a.debug_logits(9), b.debug_logits(9))
+
+
+def test_decode_steps_is_all_or_nothing():
+    shape = SHAPES["tiny"].replace(n_layers=1)
+    blob = make_weight_blob(shape, seed=4)
+    g = rl.RolloutEngine(blob, max_context=48, max_trajectories=3, kv_pool_pages=4)
+    g.append_observation([1, 2], np.arange(20), [17, 3])
+    before = [g.traj_read(t) for t in (1, 2)]
+    for args, code in [(([1, 2], 32, 1.0, 0), -6),        # trajectory 1 would reach 49 tokens
+                       (([1, 2], 30, 1.0, 0), -5),        # 47 and 33 tokens need 3 + 3 pages, 4 exist
+                       (([1, 7], 2, 1.0, 0), -2), (([1, 1], 2, 1.0, 0), -3),
+                       (([1, 2], -1, 1.0, 0), -1), (([1, 2], 2, -1.0, 0), -1)]:
+        with pytest.raises(rl.RolloutError) as ei:
+            g.decode_steps(*args)
+        assert ei.value.code == code, args
+        for t, old in zip((1, 2), before):
+            assert all(np.array_equal(x, y) for x, y in zip(g.traj_read(t), old))
+        assert g.n_free_pages() == 1
+    out, lps = g.decode_steps([1, 2], 0, 1.0, 0)
+    assert out.shape == (0, 2) and g.n_free_pages() == 1
+    out, lps = g.decode_steps([], 5, 1.0, 0)
+    assert out.shape == (5, 0)
+    out, lps = g.decode_steps([2, 1], 14, 1.0, 0)          # 17 + 31 tokens: exactly the 4 pages
+    assert out.shape == (14, 2) and g.n_free_pages() == 0 and g.traj_info(1) == (31, 2)
+
+
 # ---- cfg1: tiny fp32 decoder, free-running greedy rollout --------------------------------
 def test_cfg1_fp32_free_running_matches_oracle_golden():
     shape = SHAPES["tiny"]
