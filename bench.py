@@ -314,6 +314,8 @@ def main():
                     help="decode attention reads a forked group's shared pages once per block of members")
     ap.add_argument("--fp8-kv-cache", action="store_true",
                     help="variant, never the headline: keys / values cached as E4M3 codes (half the cache bytes)")
+    ap.add_argument("--max-batch-rows", type=int, default=0,
+                    help="rows per internal pass of an append (0: the library's default of 8192)")
     ap.add_argument("--single-step-calls", action="store_true",
                     help="one rl_decode_step call per token (the host waits for every token) instead of one "
                          "rl_decode_steps call per run of decode steps of the same trajectories")
@@ -345,7 +347,7 @@ def main():
     pages = w.n_trajectories * ((w.max_context + 15) // 16 + 2) + 64
     t0 = time.perf_counter()
     eng = rl.RolloutEngine(blob, max_context=w.max_context + 16, max_trajectories=w.n_trajectories,
-                           kv_pool_pages=pages,
+                           kv_pool_pages=pages, max_batch_rows=args.max_batch_rows,
                            flags=(rl.FLAG_SHARED_PREFIX_ATTENTION if args.shared_prefix_attention else 0) |
                            (rl.FLAG_FP8_KV_CACHE if args.fp8_kv_cache else 0))
     kv_scale = 0.5 if args.fp8_kv_cache else 1.0
