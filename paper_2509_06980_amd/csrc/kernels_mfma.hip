@@ -746,28 +746,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   }
 }
 
-// One page of the prefill kernel's online softmax for the CB column blocks of a wave.  The scores
-// stay unscaled until the exponent: 2^(S c - max c) is one fused multiply-add per score.  MASKED:
-// the page may hold keys behind some row's position (pages on the causal diagonal, and every page
-// for columns past the item's rows, whose position is -1).
-template <int CB, bool MASKED>
-__device__ __forceinline__ void prefill_page(const u32x4 (&KR)[4], const u32x4 (&VR)[4], int pg,
+// Two consecutive pages (32 keys) of the LDS-staged prefill kernel for the CB column blocks of a
+// wave.  kb / vb point at the first page's key / value block in LDS, the second page's blocks lie
+// BLK bytes behind them.  Scores: 4 x mfma 16x16x32 per page and column block.  The two pages
+// share one softmax update, and P (32 keys x 16 columns) meets the two pages' values in one
+// 16x16x32 MFMA per 16 output dims: operand slot 8 g + i of lane group g is key 4 g + i of the
+// first page for i < 4 and key 4 g + i - 4 of the second page otherwise, on both operands.
+template <int CB, bool FP8, bool MASKED>
+__device__ __forceinline__ void prefill_pair(const char* kb, const char* vb, int pg,
                                              const u32x4 (&qreg)[CB][4], f32x4 (&acc)[CB][8],
                                              float (&m)[CB], float (&l)[CB], const int (&mypos)[CB],
-                                             int g, float scale2) {
+                                             int g, int lane, float scale2) {
+  constexpr int BLK = FP8 ? 2048 : 4096, NLD = BLK / 1024;
+  f32x4 S[CB][2];
+#pragma unroll
+  for (int pp = 0; pp < 2; pp++) {
+    u32x4 raw[NLD];
+#pragma unroll
+    for (int c = 0; c < NLD; c++) raw[c] = *(const u32x4*)(kb + pp * BLK + c * 1024 + lane * 16);
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++) S[cb][pp] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+      const u32x4 kr = att_operand<FP8>(raw, c);
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++)
+        S[cb][pp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kr),
+                                                            __builtin_bit_cast(bf16x8, qreg[cb][c]),
+                                                            S[cb][pp], 0, 0, 0);
+    }
+  }
+  bf16x8 P[CB];
 #pragma unroll
   for (int cb = 0; cb < CB; cb++) {
-    f32x4 S = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int c = 0; c < 4; c++)
-      S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, KR[c]),
-                                                  __builtin_bit_cast(bf16x8, qreg[cb][c]), S, 0, 0, 0);
-    bool vis[4];
+    bool vis[8];
     float mx = ATT_NEG;
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      vis[i] = !MASKED || pg * RL_PAGE + 4 * g + i <= mypos[cb];
-      mx = fmaxf(mx, vis[i] ? S[i] : ATT_NEG);
+    for (int i = 0; i < 8; i++) {
+      vis[i] = !MASKED || (pg + (i >> 2)) * RL_PAGE + 4 * g + (i & 3) <= mypos[cb];
+      mx = fmaxf(mx, vis[i] ? S[cb][i >> 2][i & 3] : ATT_NEG);
     }
     mx = quad_max(mx);
     // m is kept in scaled units (score * scale2); scale2 > 0, so the maximum commutes with it
@@ -781,40 +798,56 @@ __device__ __forceinline__ void prefill_page(const u32x4 (&KR)[4], const u32x4 (
         for (int i = 0; i < 4; i++) acc[cb][j][i] *= alpha;
       m[cb] = mn;
     }
-    float p[4];
+    float p[8];
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], scale2, -mn));
+    for (int i = 0; i < 8; i++) {
+      p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[cb][i >> 2][i & 3], scale2, -mn));
       if (MASKED) p[i] = vis[i] ? p[i] : 0.f;
     }
-    l[cb] += (p[0] + p[1]) + (p[2] + p[3]);
-    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
-    bf16x4_t pb4 = {(__bf16)p[0], (__bf16)p[1], (__bf16)p[2], (__bf16)p[3]};
-    const s16x4 pb = __builtin_bit_cast(s16x4, pb4);
+    l[cb] += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+    P[cb] = (bf16x8){(__bf16)p[0], (__bf16)p[1], (__bf16)p[2], (__bf16)p[3],
+                     (__bf16)p[4], (__bf16)p[5], (__bf16)p[6], (__bf16)p[7]};
+  }
+  u32x4 raw0[NLD], raw1[NLD];
 #pragma unroll
-    for (int jp = 0; jp < 4; jp++) {
-      typedef __attribute__((__vector_size__(2 * sizeof(unsigned int)))) unsigned int u32x2_t;
-      const u32x2_t lo = {VR[jp][0], VR[jp][1]}, hi = {VR[jp][2], VR[jp][3]};
-      acc[cb][2 * jp] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pb,
-                                                                   acc[cb][2 * jp], 0, 0, 0);
-      acc[cb][2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pb,
-                                                                       acc[cb][2 * jp + 1], 0, 0, 0);
+  for (int c = 0; c < NLD; c++) {
+    raw0[c] = *(const u32x4*)(vb + c * 1024 + lane * 16);
+    raw1[c] = *(const u32x4*)(vb + BLK + c * 1024 + lane * 16);
+  }
+#pragma unroll
+  for (int jp = 0; jp < 4; jp++) {
+    const u32x4 v0 = att_operand<FP8>(raw0, jp), v1 = att_operand<FP8>(raw1, jp);
+    const u32x4 lo = {v0[0], v0[1], v1[0], v1[1]}, hi = {v0[2], v0[3], v1[2], v1[3]};
+#pragma unroll
+    for (int cb = 0; cb < CB; cb++) {
+      acc[cb][2 * jp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lo), P[cb],
+                                                                acc[cb][2 * jp], 0, 0, 0);
+      acc[cb][2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), P[cb],
+                                                                    acc[cb][2 * jp + 1], 0, 0, 0);
     }
   }
 }
 
-// Chunked prefill: one workgroup per (item of up to 4 * CB * 16/G rows, kv head).  Wave w owns
-// CB * 16/G consecutive rows of the item as CB blocks of 16 MFMA columns (16/G rows x the G heads
-// of the group) and walks every page those rows may see.  A page's keys / values are loaded into
-// registers once per wave and used by all CB column blocks, so every byte fetched feeds CB * 16
-// columns; the four waves read the same pages at about the same time (the later copies hit in
-// cache).  The running output is rescaled only on pages where some column's maximum moved.
-// No cross-wave merge is needed.
+// Chunked prefill with the pages staged through LDS: one workgroup per (item of up to
+// 4 * CB * 16/G rows, kv head) as above, but a page's keys / values are fetched once per
+// workgroup (not once per wave) into a double-buffered LDS stage of NP pages, in the pool's
+// operand order, and the four waves read their operands from there (linear 16-byte reads, no bank
+// conflicts).  Pages are consumed in pairs (prefill_pair).  One barrier per stage: the loads of
+// stage s + 1 are issued before the barrier of stage s and written to the other buffer after the
+// stage's arithmetic, which every wave can only reach once all waves have left stage s - 1.
+// Page indices past the item's last page are clamped to it (their keys are masked: they lie
+// behind every row of the item); the pool is cleared at load, so such blocks hold finite values.
 template <int CB, bool FP8>
-__global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void attention_prefill_lds_kernel(
     const bf16_t* __restrict__ q, const char* __restrict__ kpool, const char* __restrict__ vpool,
     const AttnItem* __restrict__ items, const int32_t* __restrict__ page_table,
     bf16_t* __restrict__ o, int nq, int nkv, int gshift, int pt_stride, float scale2) {
+  constexpr int NP = 4;
+  constexpr int BLK = FP8 ? 2048 : 4096;
+  constexpr int STAGE = 2 * NP * BLK;            // NP key blocks, then NP value blocks
+  constexpr int U = STAGE / 4096;                // 16-byte loads per thread and stage
+  __shared__ __align__(16) char s_kv[2 * STAGE];
   const int item_idx = blockIdx.x / nkv;
   const AttnItem it = items[item_idx];
   const int kvh = blockIdx.x - item_idx * nkv;
@@ -823,8 +856,10 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
   const int rpb = 16 >> gshift;                       // rows per column block
   const int wrow0 = wave * CB * rpb;                  // first row of this wave within the item
   const int wave_rows = min(it.nrows - wrow0, CB * rpb);
-  const int pg0 = 0;
   const int pg1 = wave_rows > 0 ? (it.pos0 + wrow0 + wave_rows - 1) / RL_PAGE + 1 : 0;
+  const int item_pg1 = (it.pos0 + it.nrows - 1) / RL_PAGE + 1;
+  const int pglast = item_pg1 - 1;
+  const int nst = (item_pg1 + NP - 1) / NP;
   const int32_t* pt = page_table + (size_t)it.slot * pt_stride;
   u32x4 qreg[CB][4];
   f32x4 acc[CB][8];
@@ -833,7 +868,7 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
 #pragma unroll
   for (int cb = 0; cb < CB; cb++) {
     const int r = wrow0 + cb * rpb + (n >> gshift);
-    // columns past the item's rows get position -1: every key is masked for them
+    // columns past the item's rows get position -1: every key of a masked pair is masked for them
     mypos[cb] = r < it.nrows ? it.pos0 + r : -1;
 #pragma unroll
     for (int c = 0; c < 4; c++) {
@@ -846,47 +881,50 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
     m[cb] = ATT_NEG;
     l[cb] = 0.f;
   }
-  const int pglast = max(pg1 - 1, pg0);
-  constexpr int NLD = FP8 ? 2 : 4, BLK = FP8 ? 2048 : 4096;
-  const size_t head_off = (size_t)kvh * BLK + lane * 16;
-  u32x4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
   // pages that end at or before the wave's first row are visible to all of its rows: no masking
-  const int full_pages = (it.pos0 + wrow0 + 1) / RL_PAGE;
-#define PF_PAGE_BF16(KR, VR, PG)                                              \
-  {                                                                           \
-    if ((PG) < full_pages)                                                    \
-      prefill_page<CB, false>(KR, VR, (PG), qreg, acc, m, l, mypos, g, scale2); \
-    else if ((PG) < pg1)                                                      \
-      prefill_page<CB, true>(KR, VR, (PG), qreg, acc, m, l, mypos, g, scale2); \
-  }
-#define PF_PAGE(KR, VR, PG)                                                   \
-  if constexpr (FP8) {                                                        \
-    u32x4 kx_[4], vx_[4];                                                     \
-    expand_e4m3_block(KR, kx_);                                               \
-    expand_e4m3_block(VR, vx_);                                               \
-    PF_PAGE_BF16(kx_, vx_, PG)                                                \
-  } else {                                                                    \
-    PF_PAGE_BF16(KR, VR, PG)                                                  \
-  }
-  if (pg0 < pg1) {
-    int id_cur = pt[pg0];
-    int id_nxt = pt[min(pg0 + 1, pglast)];
-    ATT_LOAD_PLAIN(kA, vA, id_cur)
-    for (int pg = pg0; pg < pg1; pg += 2) {
-      int id_n2 = pt[min(pg + 2, pglast)];
-      ATT_LOAD_PLAIN(kB, vB, id_nxt)
-      __builtin_amdgcn_sched_barrier(0);
-      PF_PAGE(kA, vA, pg)
-      __builtin_amdgcn_sched_barrier(0);
-      id_nxt = pt[min(pg + 3, pglast)];
-      ATT_LOAD_PLAIN(kA, vA, id_n2)
-      __builtin_amdgcn_sched_barrier(0);
-      PF_PAGE(kB, vB, pg + 1)
-      __builtin_amdgcn_sched_barrier(0);
+  const int full_pages = wave_rows > 0 ? (it.pos0 + wrow0 + 1) / RL_PAGE : 0;
+  u32x4 stg[U];
+  auto fetch = [&](int s) {
+    int id[NP];
+#pragma unroll
+    for (int p = 0; p < NP; p++) id[p] = pt[min(s * NP + p, pglast)];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      const int byte = u * 4096 + tid * 16;
+      const int blk = byte / BLK, off = byte % BLK;
+      const bool isv = blk >= NP;
+      const int p = isv ? blk - NP : blk;
+      int pid = id[0];
+#pragma unroll
+      for (int x = 1; x < NP; x++) pid = p == x ? id[x] : pid;
+      const char* src = (isv ? vpool : kpool) + ((size_t)pid * nkv + kvh) * BLK + off;
+      stg[u] = *(const u32x4*)src;
     }
+  };
+  auto stash = [&](int b) {
+#pragma unroll
+    for (int u = 0; u < U; u++) *(u32x4*)(s_kv + b * STAGE + u * 4096 + tid * 16) = stg[u];
+  };
+  if (nst > 0) {
+    fetch(0);
+    stash(0);
   }
-#undef PF_PAGE
-#undef PF_PAGE_BF16
+  for (int s = 0; s < nst; s++) {
+    if (s + 1 < nst) fetch(s + 1);
+    __syncthreads();
+    const char* buf = s_kv + (s & 1) * STAGE;
+#pragma unroll
+    for (int j = 0; j < NP / 2; j++) {
+      const int pg = s * NP + 2 * j;
+      const char* kb = buf + 2 * j * BLK;
+      const char* vb = buf + (NP + 2 * j) * BLK;
+      if (pg + 1 < full_pages)
+        prefill_pair<CB, FP8, false>(kb, vb, pg, qreg, acc, m, l, mypos, g, lane, scale2);
+      else if (pg < pg1)
+        prefill_pair<CB, FP8, true>(kb, vb, pg, qreg, acc, m, l, mypos, g, lane, scale2);
+    }
+    if (s + 1 < nst) stash((s + 1) & 1);
+  }
 #pragma unroll
   for (int cb = 0; cb < CB; cb++) {
     const float lt = quad_sum(l[cb]);
@@ -900,7 +938,6 @@ __global__ __launch_bounds__(256) void attention_prefill_mfma_kernel(
         uint2 w;
         w.x = (uint32_t)f2bf(acc[cb][jb][0] * inv) | ((uint32_t)f2bf(acc[cb][jb][1] * inv) << 16);
         w.y = (uint32_t)f2bf(acc[cb][jb][2] * inv) | ((uint32_t)f2bf(acc[cb][jb][3] * inv) << 16);
-        // k advances by 16 per jb: two A-tile k-blocks of 16 per 32 dims => +1 k-block each step
         *(uint2*)(o + base + (size_t)jb * (4 * 64 * 8)) = w;
       }
     }
@@ -967,10 +1004,10 @@ void launch_attention_mfma(hipStream_t s, const bf16_t* q, KvPool pool, const At
   const dim3 grid(n_items * md.nkv);
   if (prefill) {
     if (md.kv_fp8)
-      attention_prefill_mfma_kernel<RL_PREFILL_CB, true><<<grid, 256, 0, s>>>(
+      attention_prefill_lds_kernel<RL_PREFILL_CB, true><<<grid, 256, 0, s>>>(
           q, kp, vp, items, page_table, o, md.nq, md.nkv, gshift, md.max_pages_per_traj, scale2);
     else
-      attention_prefill_mfma_kernel<RL_PREFILL_CB, false><<<grid, 256, 0, s>>>(
+      attention_prefill_lds_kernel<RL_PREFILL_CB, false><<<grid, 256, 0, s>>>(
           q, kp, vp, items, page_table, o, md.nq, md.nkv, gshift, md.max_pages_per_traj, scale2);
     return;
   }
