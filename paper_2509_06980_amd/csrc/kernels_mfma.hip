@@ -786,10 +786,15 @@ __device__ __forceinline__ void prefill_pair(const char* kb, const char* vb, int
       vis[i] = !MASKED || (pg + (i >> 2)) * RL_PAGE + 4 * g + (i & 3) <= mypos[cb];
       mx = fmaxf(mx, vis[i] ? S[cb][i >> 2][i & 3] : ATT_NEG);
     }
-    mx = quad_max(mx);
-    // m is kept in scaled units (score * scale2); scale2 > 0, so the maximum commutes with it
-    const float mn = fmaxf(m[cb], mx * scale2);
-    if (__any(mn > m[cb])) {
+    // m (in scaled units: score * scale2, scale2 > 0) is the reference point of the exponents, not
+    // necessarily the running maximum: it only moves, to the column's maximum so far, when some
+    // score of the wave lies more than kLazy above it.  Every term then stays below 2^kLazy, the
+    // ratio acc / l does not depend on m, and the common case needs neither the reduction over
+    // the column's four lanes nor a rescaling of the accumulators.
+    constexpr float kLazy = 8.0f;
+    if (__any(mx * scale2 > m[cb] + kLazy)) {
+      mx = quad_max(mx);
+      const float mn = fmaxf(m[cb], mx * scale2);
       const float alpha = exp2f(m[cb] - mn);
       l[cb] *= alpha;
 #pragma unroll
@@ -798,6 +803,7 @@ __device__ __forceinline__ void prefill_pair(const char* kb, const char* vb, int
         for (int i = 0; i < 4; i++) acc[cb][j][i] *= alpha;
       m[cb] = mn;
     }
+    const float mn = m[cb];
     float p[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) {
@@ -808,22 +814,38 @@ __device__ __forceinline__ void prefill_pair(const char* kb, const char* vb, int
     P[cb] = (bf16x8){(__bf16)p[0], (__bf16)p[1], (__bf16)p[2], (__bf16)p[3],
                      (__bf16)p[4], (__bf16)p[5], (__bf16)p[6], (__bf16)p[7]};
   }
-  u32x4 raw0[NLD], raw1[NLD];
+  if constexpr (FP8) {
+    u32x4 raw0[NLD], raw1[NLD];
 #pragma unroll
-  for (int c = 0; c < NLD; c++) {
-    raw0[c] = *(const u32x4*)(vb + c * 1024 + lane * 16);
-    raw1[c] = *(const u32x4*)(vb + BLK + c * 1024 + lane * 16);
-  }
+    for (int c = 0; c < NLD; c++) {
+      raw0[c] = *(const u32x4*)(vb + c * 1024 + lane * 16);
+      raw1[c] = *(const u32x4*)(vb + BLK + c * 1024 + lane * 16);
+    }
 #pragma unroll
-  for (int jp = 0; jp < 4; jp++) {
-    const u32x4 v0 = att_operand<FP8>(raw0, jp), v1 = att_operand<FP8>(raw1, jp);
-    const u32x4 lo = {v0[0], v0[1], v1[0], v1[1]}, hi = {v0[2], v0[3], v1[2], v1[3]};
+    for (int jb = 0; jb < 8; jb++) {
+      uint32_t a0, b0, a1, b1;
+      e4m3x4_to_bf16(raw0[jb >> 2][jb & 3], &a0, &b0);
+      e4m3x4_to_bf16(raw1[jb >> 2][jb & 3], &a1, &b1);
+      const bf16x8 vo = __builtin_bit_cast(bf16x8, ((u32x4){a0, b0, a1, b1}));
 #pragma unroll
-    for (int cb = 0; cb < CB; cb++) {
-      acc[cb][2 * jp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lo), P[cb],
-                                                                acc[cb][2 * jp], 0, 0, 0);
-      acc[cb][2 * jp + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), P[cb],
-                                                                    acc[cb][2 * jp + 1], 0, 0, 0);
+      for (int cb = 0; cb < CB; cb++)
+        acc[cb][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vo, P[cb], acc[cb][jb], 0, 0, 0);
+    }
+  } else {
+    // the lane's 4 tokens of 16 output dims are 8 bytes in each page's block: two 8-byte reads
+    // make the 32-key operand without any register shuffling
+    uint2 v0[8], v1[8];
+#pragma unroll
+    for (int jb = 0; jb < 8; jb++) {
+      v0[jb] = *(const uint2*)(vb + (jb >> 1) * 1024 + lane * 16 + (jb & 1) * 8);
+      v1[jb] = *(const uint2*)(vb + BLK + (jb >> 1) * 1024 + lane * 16 + (jb & 1) * 8);
+    }
+#pragma unroll
+    for (int jb = 0; jb < 8; jb++) {
+      const bf16x8 vo = __builtin_bit_cast(bf16x8, ((u32x4){v0[jb].x, v0[jb].y, v1[jb].x, v1[jb].y}));
+#pragma unroll
+      for (int cb = 0; cb < CB; cb++)
+        acc[cb][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vo, P[cb], acc[cb][jb], 0, 0, 0);
     }
   }
 }
