@@ -245,13 +245,40 @@ __global__ __launch_bounds__(64 * NW) void gemm_mfma_kernel(const bf16_t* __rest
 // GEMM for many rows (chunked prefill, teacher-forced passes) and wide outputs: tile 256 x 256,
 // 4 waves as 2 x 2, wave tile 128 x 128 (16 accumulators of 32x32).  Per 16-k step a wave reads 4
 // row and 4 column operands from LDS for 16 MFMAs, so an operand byte fetched through the L1 feeds
-// twice the MFMAs of the 128 x 128 kernel above (whose limit at 8192 rows is the L1, not the matrix
-// pipes).  Both operands are staged through LDS (double buffered, 2 x 64 KB); the next chunk
-// travels HBM -> registers while the current one is consumed.  The k order per output element is
-// that of the 128 x 128 kernel: results are bit-identical.  Measured at 8192 rows: N = 6144
-// +10 %, N = 19456 +4.5 %, N = 24576 (K 4096) +12 %, N = 4096 (K 12288) +12 %; slower for N = 2560
-// (320 workgroups on 256 CUs), which keeps the kernel above.  K / 64 must be even; no split-K.
+// twice the MFMAs of the 128 x 128 kernel above.  Both operands are staged through LDS (double
+// buffered, 2 x 64 KB).
+// The loop is one steady stream: a chunk is 16 pieces of 16 bytes per thread, and every group of
+// 4 MFMAs carries one global load (a piece 24 groups = 1.5 chunks ahead of the store that needs
+// it, in a ring of 32 register slots), the LDS stores of the next chunk (all done by group 11),
+// and two of the eight LDS operand reads of the next 16-k step.  The workgroup barrier sits in
+// front of group 12: by then the next chunk is complete in the other buffer and this buffer has
+// been read out, so groups 12-15 already fetch the next chunk's first operands and no LDS latency
+// is exposed at the chunk boundary.  A burst of 16 loads per thread at the top of every chunk
+// (all 256 workgroups at about the same time) instead of this even stream costs 17-26 %.
+// sched_group_barrier pins the interleaving (MFMA, load, MFMA, stores, MFMA, reads, MFMA).
+// XCD-aware tile numbering (xcd_tile256) is worth another 1.5-3 %.
+// The k order per output element is that of the 128 x 128 kernel: results are bit-identical.
+// Measured at 8192 rows (us, before -> after the steady stream): N = 6144 K = 2560 310 -> 266,
+// N = 19456 K = 2560 1010 -> 843, N = 24576 K = 4096 1800 -> 1462, N = 4096 K = 12288 830 -> 656;
+// N = 2560 stays with the kernel above (320 workgroups on 256 CUs).  K / 64 must be even; no
+// split-K.
 // =============================================================================================
+// Tile of a workgroup: the hardware hands workgroups to the 8 XCDs round-robin by linear index
+// and each XCD has its own L2.  XCD x works through a contiguous range of a sequence that walks
+// groups of 4 row tiles column by column, so the 32 workgroups resident on an XCD cover a
+// compact block of 4 x 8 tiles (12 distinct operand tiles per chunk instead of ~22).  A
+// bijection for any tile counts.
+__device__ __forceinline__ void xcd_tile256(int id, int tiles_m, int tiles_n, int* tm, int* tn) {
+  constexpr int GM = 4;
+  const int total = tiles_m * tiles_n;
+  const int base = total >> 3, rem = total & 7, x = id & 7;
+  const int vid = x * base + min(x, rem) + (id >> 3);
+  const int per_group = GM * tiles_n, grp = vid / per_group, first = grp * GM;
+  const int gm = min(GM, tiles_m - first), within = vid - grp * per_group;
+  *tm = first + within % gm;
+  *tn = within / gm;
+}
+
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm256_mfma_kernel(const bf16_t* __restrict__ A,
                                                       const bf16_t* __restrict__ Wp,
@@ -262,10 +289,12 @@ __global__ __launch_bounds__(256) void gemm256_mfma_kernel(const bf16_t* __restr
   const int NB = N >> 5;
   const int nchunks = K >> 6;
   const int mtiles128 = (M + 127) >> 7;
-  const int mt0 = blockIdx.y * 2, mt1 = min(mt0 + 1, mtiles128 - 1);   // second half clamped (results dropped)
+  int bx, by;
+  xcd_tile256(blockIdx.y * gridDim.x + blockIdx.x, gridDim.y, gridDim.x, &by, &bx);
+  const int mt0 = by * 2, mt1 = min(mt0 + 1, mtiles128 - 1);   // second half clamped (results dropped)
   const u32x4* Ag0 = (const u32x4*)(A + (size_t)mt0 * K * 128);
   const u32x4* Ag1 = (const u32x4*)(A + (size_t)mt1 * K * 128);
-  const int strip0 = blockIdx.x * 8;
+  const int strip0 = bx * 8;
   // weight pieces of this thread: 2048 pieces per chunk = 8 strips x 256; piece p = i * 256 + tid
   // strips past the end (N not a multiple of 256) are clamped to the last one; results dropped
   const int nvalid = min(8, NB - strip0);
@@ -278,67 +307,76 @@ __global__ __launch_bounds__(256) void gemm256_mfma_kernel(const bf16_t* __restr
     for (int b = 0; b < 4; b++)
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[a][b][e] = 0.f;
-  u32x4 ra[2][8], rb[2][8];
-#define G_LOAD(S, CHUNK)                                                     \
-  {                                                                          \
-    const int cl_ = min((CHUNK), nchunks - 1);                               \
-    _Pragma("unroll") for (int i = 0; i < 4; i++) {                          \
-      ra[S][i] = Ag0[(size_t)cl_ * 1024 + i * 256 + tid];                    \
-      ra[S][4 + i] = Ag1[(size_t)cl_ * 1024 + i * 256 + tid];                \
-    }                                                                        \
-    _Pragma("unroll") for (int i = 0; i < 8; i++) rb[S][i] = Wg[(size_t)cl_ * NB * 256 + wbase + min(i, nvalid - 1) * 256]; \
-    __builtin_amdgcn_sched_barrier(0);                                       \
+  // the 16 pieces of a thread and chunk: 0-3 rows 0-127, 4-7 rows 128-255, 8-15 the 8 strips;
+  // chunks past the end are clamped to the last one (re-reads that hit in cache, never used)
+  auto piece_src = [&](int chunk, int p) -> const u32x4* {
+    const int cl = min(chunk, nchunks - 1);
+    if (p < 4) return Ag0 + (size_t)cl * 1024 + p * 256 + tid;
+    if (p < 8) return Ag1 + (size_t)cl * 1024 + (p - 4) * 256 + tid;
+    return Wg + (size_t)cl * NB * 256 + wbase + min(p - 8, nvalid - 1) * 256;
+  };
+  auto piece_dst = [&](int buf, int p) -> u32x4* {
+    return smem + buf * 4096 + (p < 8 ? p * 256 : 2048 + (p - 8) * 256) + tid;
+  };
+  constexpr int DIST = 24;                   // groups between a piece's load and the group of piece p's store
+  u32x4 rs[32];                              // ring: the load of group T (counted from chunk 0) lands in slot T % 32
+  u32x4 av[2][4], bv[2][4];
+  {
+    u32x4 t0[16];
+#pragma unroll
+    for (int p = 0; p < 16; p++) t0[p] = *piece_src(0, p);
+#pragma unroll
+    for (int q = 0; q < DIST; q++) rs[(q + 32 - DIST) & 31] = *piece_src(1 + (q >> 4), q & 15);
+#pragma unroll
+    for (int p = 0; p < 16; p++) *piece_dst(0, p) = t0[p];
   }
-#define G_STORE(S, BUF, I0, I1)                                              \
-  {                                                                          \
-    u32x4* as_w = smem + (BUF) * 4096;                                       \
-    u32x4* bs_w = as_w + 2048;                                               \
-    _Pragma("unroll") for (int i = (I0); i < (I1); i++) { as_w[i * 256 + tid] = ra[S][i]; bs_w[i * 256 + tid] = rb[S][i]; } \
-  }
-#define G_COMPUTE(KK)                                                        \
-  {                                                                          \
-    if ((KK) < 3) {                                                          \
-      _Pragma("unroll") for (int x = 0; x < 4; x++) {                        \
-        av[((KK) + 1) & 1][x] = as_[(((KK) + 1) * 4 + x) * 64 + lane];       \
-        bv[((KK) + 1) & 1][x] = bs_[(x * 4 + (KK) + 1) * 64 + lane];         \
-      }                                                                      \
-    }                                                                        \
-    __builtin_amdgcn_sched_barrier(0);                                       \
-    _Pragma("unroll") for (int a = 0; a < 4; a++)                            \
-      _Pragma("unroll") for (int b = 0; b < 4; b++)                          \
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[(KK) & 1][a]), \
-                                                            __builtin_bit_cast(bf16x8, bv[(KK) & 1][b]), \
-                                                            acc[a][b], 0, 0, 0); \
-    __builtin_amdgcn_sched_barrier(0);                                       \
-  }
-#define G_ITER(S, CC)                                                        \
-  {                                                                          \
-    /* chunk CC is in LDS buffer S; registers 1-S hold chunk CC+1; chunk CC+2 starts its trip into registers S */ \
-    G_LOAD(S, (CC) + 2)                                                      \
-    const u32x4* as_ = smem + (S) * 4096 + wm * 1024;                        \
-    const u32x4* bs_ = smem + (S) * 4096 + 2048 + wn * 1024;                 \
-    u32x4 av[2][4], bv[2][4];                                                \
-    _Pragma("unroll") for (int x = 0; x < 4; x++) { av[0][x] = as_[x * 64 + lane]; bv[0][x] = bs_[(x * 4) * 64 + lane]; } \
-    G_COMPUTE(0)                                                             \
-    G_COMPUTE(1)                                                             \
-    G_STORE(1 - (S), 1 - (S), 0, 4)                                          \
-    G_COMPUTE(2)                                                             \
-    G_STORE(1 - (S), 1 - (S), 4, 8)                                          \
-    G_COMPUTE(3)                                                             \
-    __syncthreads();                                                         \
-  }
-  G_LOAD(0, 0)
-  G_LOAD(1, 1)
-  G_STORE(0, 0, 0, 8)
   __syncthreads();
-  for (int c = 0; c < nchunks; c += 2) {   // nchunks is even (checked by the launcher)
-    G_ITER(0, c)
-    G_ITER(1, c + 1)
+  {
+    const u32x4* as_ = smem + wm * 1024;
+    const u32x4* bs_ = smem + 2048 + wn * 1024;
+#pragma unroll
+    for (int x = 0; x < 4; x++) { av[0][x] = as_[x * 64 + lane]; bv[0][x] = bs_[(x * 4) * 64 + lane]; }
   }
-#undef G_LOAD
-#undef G_STORE
-#undef G_COMPUTE
-#undef G_ITER
+  for (int c = 0; c < nchunks; c += 2) {   // nchunks is even (checked by the launcher)
+#pragma unroll
+    for (int it2 = 0; it2 < 2; it2++) {
+      const int i = c + it2;               // chunk being multiplied; it sits in LDS buffer it2
+      const u32x4* as_cur = smem + it2 * 4096 + wm * 1024;
+      const u32x4* bs_cur = smem + it2 * 4096 + 2048 + wn * 1024;
+      const u32x4* as_nxt = smem + (1 - it2) * 4096 + wm * 1024;
+      const u32x4* bs_nxt = smem + (1 - it2) * 4096 + 2048 + wn * 1024;
+#pragma unroll
+      for (int g = 0; g < 16; g++) {
+        const int kk = g >> 2, a = g & 3;
+        if (g == 12) __syncthreads();      // chunk i + 1 is complete in the other buffer; this one is read out
+        rs[(16 * it2 + g) & 31] = *piece_src(i + 1 + ((g + DIST) >> 4), (g + DIST) & 15);
+        // stores of chunk i + 1: pieces p with 3 p / 4 == g (16 pieces over groups 0-11)
+#pragma unroll
+        for (int p = 0; p < 16; p++)
+          if ((3 * p) / 4 == g) *piece_dst(1 - it2, p) = rs[(16 * it2 + p + 32 - DIST) & 31];
+        // operands of the next 16-k step
+        if (kk < 3) {
+          av[(kk + 1) & 1][a] = as_cur[((kk + 1) * 4 + a) * 64 + lane];
+          bv[(kk + 1) & 1][a] = bs_cur[(a * 4 + kk + 1) * 64 + lane];
+        } else {
+          av[0][a] = as_nxt[a * 64 + lane];
+          bv[0][a] = bs_nxt[(a * 4) * 64 + lane];
+        }
+#pragma unroll
+        for (int b = 0; b < 4; b++)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[kk & 1][a]),
+                                                              __builtin_bit_cast(bf16x8, bv[kk & 1][b]),
+                                                              acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);   // LDS stores
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+    }
+  }
   float* Cp = (float*)Cv;
 #pragma unroll
   for (int b = 0; b < 4; b++) {
