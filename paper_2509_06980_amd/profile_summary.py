@@ -114,7 +114,7 @@ def mfma_table(counter_path, trace_path):
     print("# Matrix-core (MFMA) utilisation of the chunked-prefill kernels and the decode GEMMs "
           "(Qwen3-4B shape, 128 trajectories)\n")
     print("Commands (MI355X box, repository root; counters and durations in separate runs of the same command):\n")
-    print("    rocprofv3 --pmc SQ_INSTS_VALU_MFMA_MOPS_BF16 --kernel-include-regex 'gemm_mfma|attention' "
+    print("    rocprofv3 --pmc SQ_INSTS_VALU_MFMA_MOPS_BF16 --kernel-include-regex 'gemm|attention' "
           "--output-format csv -d out/pmc_mfma -o m -- python3 bench.py --warmup 0 --no-cpu-baseline --scale 0.5")
     print("    rocprofv3 --kernel-trace --output-format csv -d out/trace_half -o t -- python3 bench.py --warmup 0 "
           "--no-cpu-baseline --scale 0.5")
@@ -165,7 +165,7 @@ def rollout_summary(trace_path, stats_path, bench_log):
           "trajectory x kv head) by launch shape, from the kernel trace:\n")
     trace_summary(trace_path)
     print("\nThe decode average agrees with the HIP-event figure of bench.py (the profiler adds a little "
-          "per-launch overhead to the event bracket). Chunked prefill runs in attention_prefill_mfma_kernel.\n")
+          "per-launch overhead to the event bracket). Chunked prefill runs in attention_prefill_lds_kernel.\n")
     print("| kernel | calls | total ms | avg us | % |\n|---|---|---|---|---|")
     with open(stats_path, newline="") as f:
         for x in csv.DictReader(f):
@@ -202,11 +202,11 @@ def stall_table(path_a, path_b):
     print("# Stall profile of the GEMM and attention kernels (Qwen3-4B shape, 128 trajectories, half lengths)\n")
     print("Commands (MI355X box, repository root; two counter sets, one run each):\n")
     print("    rocprofv3 --pmc SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_WAIT_INST_LDS SQ_WAIT_INST_ANY "
-          "SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE --kernel-include-regex 'gemm_mfma|attention' --output-format csv "
+          "SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE --kernel-include-regex 'gemm|attention' --output-format csv "
           "-d out/pmc_sq_a -o a -- python3 bench.py --warmup 0 --no-cpu-baseline --scale 0.5")
     print("    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_LDS_DATA_FIFO_FULL SQ_LDS_CMD_FIFO_FULL TA_TA_BUSY_sum "
           "TA_ADDR_STALLED_BY_TC_CYCLES_sum TCP_PENDING_STALL_CYCLES_sum TCP_TCP_TA_DATA_STALL_CYCLES_sum "
-          "--kernel-include-regex 'gemm_mfma|attention' --output-format csv -d out/pmc_sq_b -o b -- python3 bench.py "
+          "--kernel-include-regex 'gemm|attention' --output-format csv -d out/pmc_sq_b -o b -- python3 bench.py "
           "--warmup 0 --no-cpu-baseline --scale 0.5")
     print("    python -m paper_2509_06980_amd.profile_summary --stalls <a_counter_collection.csv> <b_counter_collection.csv>\n")
     print("GRBM_GUI_ACTIVE is summed over the 8 XCDs; durations are those of the counter run (kernels run one at a "
