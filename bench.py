@@ -188,6 +188,23 @@ def run_rollout(engine, w, shape, stats, fuse_appends=False, kv_scale=1.0, singl
     return n_gen
 
 
+def merge_turns(turns, limit=12):
+    """The per-turn decode figures; with more runs of decode steps than `limit` (ragged workloads,
+    where every finished trajectory starts a new run) consecutive runs are summed into `limit`
+    groups so that the JSON line stays short."""
+    if len(turns) <= limit:
+        return turns
+    out = []
+    per = -(-len(turns) // limit)
+    for a in range(0, len(turns), per):
+        grp = turns[a:a + per]
+        out.append({"ctx_first": grp[0]["ctx_first"], "ctx_last": grp[-1]["ctx_last"],
+                    "steps": sum(t["steps"] for t in grp), "tokens": sum(t["tokens"] for t in grp),
+                    "s": sum(t["s"] for t in grp), "bytes": sum(t["bytes"] for t in grp),
+                    "bytes_traj": sum(t["bytes_traj"] for t in grp)})
+    return out
+
+
 def append_mfma(stats, shape):
     """Dense-contraction rate of the chunked prefill (appends + forks, wall time): linear layers of
     every appended row plus causal attention (QK^T and PV) over the keys each row sees."""
@@ -438,7 +455,7 @@ def main():
              "hbm_GBs": round(t["bytes"] / t["s"] / 1e9, 1),
              "hbm_frac": round(t["bytes"] / t["s"] / 1e9 / HBM_PEAK_GBS, 4),
              "hbm_GBs_counting_shared_pages_per_trajectory": round(t["bytes_traj"] / t["s"] / 1e9, 1)}
-            for t in stats.get("turns", [])],
+            for t in merge_turns(stats.get("turns", []))],
         "append_mfma": append_mfma(stats, shape),
         "append_s_per_step": round(stats["append_s"] / max(args.steps, 1), 3),
         "decode_s_per_step": round(stats["decode_s"] / max(args.steps, 1), 3),
