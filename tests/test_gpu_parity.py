@@ -465,6 +465,35 @@ def test_mfma_long_context_split_attention_and_chunked_prefill():
         compare_records(o, g, t)
 
 
+@pytest.mark.parametrize("name", ["small-d128", "small-g1", "small-g2", "small-g8"])
+def test_chunked_prefill_page_pair_stage_and_item_edges(name):
+    # the prefill kernel consumes pages in pairs from LDS stages of four pages, in items of
+    # 4 waves x 2 blocks x 16/G rows: append lengths and starting positions chosen so that contexts
+    # end on odd and even page counts, on and next to stage boundaries (64 tokens), items are
+    # ragged (1 row, one row more or less than a block / an item) and later chunks start at
+    # positions that are not page aligned, on top of keys cached by earlier chunks
+    shape = SHAPES[name]
+    blob = make_weight_blob(shape, seed=11, weight_std=0.03, gain_std=0.1)
+    o, g = _pair(shape, blob, max_context=512, max_trajectories=8, kv_pool_pages=256)
+    rng = np.random.default_rng(4)
+    traj = [0, 1, 2, 3, 4, 5]
+    rounds = [[1, 15, 17, 33, 64, 65], [63, 1, 47, 31, 1, 130], [2, 97, 16, 129, 66, 3]]
+    for lens in rounds:
+        toks = rng.integers(0, shape.vocab, sum(lens))
+        for e in (o, g):
+            e.append_observation(traj, toks, lens)
+        worst = max(float(np.abs(o.debug_logits(t) - g.debug_logits(t)).max()) for t in traj)
+        assert worst < TOL_BF16, (name, lens, worst)
+        ids, lps = o.decode_step(traj, 1.0, 9)
+        glp = g.decode_step_forced(traj, 1.0, ids)
+        assert np.abs(glp - lps).max() < TOL_BF16
+    for t in traj:
+        compare_records(o, g, t)
+    # the masked log-prob pass walks the same contexts in one teacher-forced prefill
+    ro, rg = o.recompute_logprobs(traj, 1.0), g.recompute_logprobs(traj, 1.0)
+    assert np.abs(np.asarray(ro) - np.asarray(rg)).max() < TOL_BF16
+
+
 def test_ragged_workload_integer_state_bit_exact():
     # cfg4 shape of workload (ragged turns, shrinking batch) at reduced lengths, tiny fp32 model
     shape = SHAPES["tiny"].replace(n_layers=1)
