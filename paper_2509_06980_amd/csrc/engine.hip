@@ -455,7 +455,10 @@ int add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {  
   int64_t total_pages = 0;
   for (int i = 0; i < n; i++) total_pages += st.pos[i] / RL_PAGE + 1 - own_lo[i];
   for (auto& b : blocks) total_pages += b.pages;
-  int chunk = (int)std::max<int64_t>(16, (total_pages * m->md.nkv + kAttnTargetWgs - 1) / kAttnTargetWgs);
+  // enough (trajectory, kv head) pairs to put two workgroups on every CU: cut only what is longer
+  // than the average (no parts, hence no merge launch, when the lengths are alike)
+  const int target_wgs = (int64_t)n * m->md.nkv >= 512 ? 512 : kAttnTargetWgs;
+  int chunk = (int)std::max<int64_t>(16, (total_pages * m->md.nkv + target_wgs - 1) / target_wgs);
   int next_part = 0;
   for (auto& b : blocks) {
     int parts = (b.pages + chunk - 1) / chunk;
