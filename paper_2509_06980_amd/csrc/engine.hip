@@ -219,7 +219,10 @@ GemmPlan plan_gemm(int M, int N, int K, bool can_split, size_t part_rows) {
     s = (target + tiles / 2) / tiles;
     s = std::min({s, max_splits, std::max(1, K / 256), (int)std::min<size_t>(part_rows / (size_t)M, 64)});
   }
-  return GemmPlan{4, std::max(1, s)};
+  // narrow outputs (small models): 64-column tiles when 128-column tiles times slices leave more
+  // than half of the CUs without a workgroup
+  s = std::max(1, s);
+  return GemmPlan{tiles * s < 160 && N <= 8192 && M <= 128 ? 2 : 4, s};
 }
 
 // Leaves the last down-projection as m->pending_parts partial sums in m->ph (added by the next
