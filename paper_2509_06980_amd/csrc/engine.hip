@@ -458,10 +458,32 @@ int add_decode_items(rl_model* m, Staging& st, const std::vector<Traj*>& ts) {  
   int64_t total_pages = 0;
   for (int i = 0; i < n; i++) total_pages += st.pos[i] / RL_PAGE + 1 - own_lo[i];
   for (auto& b : blocks) total_pages += b.pages;
-  // enough (trajectory, kv head) pairs to put two workgroups on every CU: cut only what is longer
-  // than the average (no parts, hence no merge launch, when the lengths are alike)
-  const int target_wgs = (int64_t)n * m->md.nkv >= 512 ? 512 : kAttnTargetWgs;
-  int chunk = (int)std::max<int64_t>(16, (total_pages * m->md.nkv + target_wgs - 1) / target_wgs);
+  // Contexts of about equal length are cut into parts only when that is expected to pay.  Uncut, the launch lasts as long as
+  // its longest item streams on one workgroup (about 0.28 us per 16-token page of one kv head) or
+  // as long as all pages take at the bandwidth of the chip (1.37 ns per page and kv head at
+  // 6 TB/s), whichever is more; cut into ~kAttnTargetWgs even shares it is bandwidth bound but
+  // pays for the merge launch, the partial results and the shorter loops (about 19 us in all).
+  // Constants fitted on the 4B shape at 4 to 96 trajectories and contexts of 512 to 6144 tokens
+  // (break-even at 12 trajectories of 2048 tokens and at 21 of 6144); always cutting below 1024
+  // (trajectory, kv head) pairs cost 5-15 % of the decode step at 32 to 56 equal trajectories,
+  // never cutting 23 % at 8 trajectories of 6144 tokens.
+  int pages_max = 0;
+  for (int i = 0; i < n; i++) pages_max = std::max(pages_max, st.pos[i] / RL_PAGE + 1 - own_lo[i]);
+  for (auto& b : blocks) pages_max = std::max(pages_max, b.pages);
+  const double units = (double)total_pages * m->md.nkv;
+  const int n_items = n + (int)blocks.size();
+  const bool alike = (int64_t)pages_max * n_items * 2 <= total_pages * 3;   // longest <= 1.5 x average
+  int chunk;
+  if (alike) {
+    const bool cut = m->mfma && 0.28 * pages_max > 0.00137 * units + 19.0;
+    chunk = cut ? (int)std::max<int64_t>(16, (total_pages * m->md.nkv + kAttnTargetWgs - 1) / kAttnTargetWgs)
+                : std::max(16, pages_max);
+  } else {
+    // ragged lengths: even shares; with 512 or more (trajectory, kv head) pairs only what is
+    // longer than twice the average is cut
+    const int target_wgs = (int64_t)n * m->md.nkv >= 512 ? 512 : kAttnTargetWgs;
+    chunk = (int)std::max<int64_t>(16, (total_pages * m->md.nkv + target_wgs - 1) / target_wgs);
+  }
   int next_part = 0;
   for (auto& b : blocks) {
     int parts = (b.pages + chunk - 1) / chunk;

@@ -449,9 +449,9 @@ def test_mfma_long_context_split_attention_and_chunked_prefill():
     # row budget that forces several prefill passes and splits a trajectory across passes
     shape = SHAPES["small-d128"]
     blob = make_weight_blob(shape, seed=3, weight_std=0.03, gain_std=0.1)
-    o, g = _pair(shape, blob, max_context=1024, max_trajectories=4, kv_pool_pages=200, max_batch_rows=384)
+    o, g = _pair(shape, blob, max_context=2048, max_trajectories=4, kv_pool_pages=200, max_batch_rows=384)
     rng = np.random.default_rng(1)
-    lens = [700, 523]
+    lens = [1700, 523]      # 107 pages against 33: the planner cuts the long context into parts
     toks = rng.integers(0, shape.vocab, sum(lens))
     for e in (o, g):
         e.append_observation([0, 1], toks, lens)
@@ -882,9 +882,9 @@ def test_fp8_kv_cache_lockstep(name):
 def test_fp8_kv_cache_long_context_split_attention_chunked_prefill_and_mixed_pass():
     shape = SHAPES["small-d128"]
     blob = make_weight_blob(shape, seed=3, weight_std=0.03, gain_std=0.1)
-    o, g = _fp8_pair(shape, blob, max_context=1024, max_trajectories=4, kv_pool_pages=200, max_batch_rows=384)
+    o, g = _fp8_pair(shape, blob, max_context=2048, max_trajectories=4, kv_pool_pages=200, max_batch_rows=384)
     rng = np.random.default_rng(1)
-    lens = [700, 523]
+    lens = [1700, 523]      # 107 pages against 33: the planner cuts the long context into parts
     toks = rng.integers(0, shape.vocab, sum(lens))
     for e in (o, g):
         e.append_observation([0, 1], toks, lens)
